@@ -1,0 +1,171 @@
+"""ctypes front end of the MXInt CPU oracle (``mx_oracle.c``) -- TEST INFRASTRUCTURE ONLY.
+
+Nothing in the GPU library imports this module; only the tests, the smoke check
+and the CPU-baseline leg of the benchmark do.  Every function here only
+marshals numpy arrays into the plain C routines; the arithmetic (and the
+statement of what the paper fixes and what is a reading of it) lives in the C
+file.
+
+Format arguments follow Section 4.1 of the paper: ``block`` elements share one
+``e``-bit exponent; ``w`` is the stored width of an element, i.e. the paper's
+mantissa width m plus the sign bit (Eq. 1).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mx_oracle.c")
+_LIB = os.path.join(_HERE, "libmx_oracle.so")
+
+RNE = 0
+RTZ = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2, no intrinsics)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+             "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, i32, p = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.mxo_quantize.argtypes = [p, i64, i64, i64, i32, i32, i32, i32, p, p]
+        lib.mxo_quantize_axis0.argtypes = [p, i64, i64, i64, i32, i32, i32, i32, p, p]
+        lib.mxo_dequantize.argtypes = [p, p, i64, i64, i32, i32, i32, p]
+        lib.mxo_pack_bits.argtypes = [p, i64, i64, i32, p]
+        lib.mxo_unpack_bits.argtypes = [p, i64, i64, i32, p]
+        lib.mxo_gemm.argtypes = [p, p, i32, p, p, i32, i64, i64, i64, i32, i32, i64, i64, p, p]
+        lib.mxo_set_threads.argtypes = [i32]
+        for f in (lib.mxo_quantize, lib.mxo_quantize_axis0, lib.mxo_dequantize, lib.mxo_pack_bits,
+                  lib.mxo_unpack_bits, lib.mxo_gemm, lib.mxo_set_threads):
+            f.restype = i32
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc: int, what: str):
+    if rc == 1:
+        raise ValueError("%s: bad argument" % what)
+    if rc == 2:
+        raise ValueError("%s: input holds a NaN or an infinity" % what)
+    if rc != 0:
+        raise RuntimeError("%s: status %d" % (what, rc))
+
+
+def set_threads(n: int) -> int:
+    """Set the number of OpenMP threads the row loops use; returns the count in force."""
+    return int(_load().mxo_set_threads(int(n)))
+
+
+def quantize(x: np.ndarray, block: int, w: int, e: int = 8, rounding: int = RNE,
+             axis: int = 1) -> Tuple[np.ndarray, np.ndarray]:
+    """Quantize a 2-D float32 array to MXInt.
+
+    axis=1: blocks along each row; returns q int8 [rows, cols], exps uint8 [rows, cols/block].
+    axis=0: blocks down each column; returns the quantization of x.T:
+            q int8 [cols, rows], exps uint8 [cols, rows/block].
+    """
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.ndim == 2
+    rows, cols = x.shape
+    lib = _load()
+    if axis == 1:
+        if block < 1 or cols % block:
+            raise ValueError("cols must be a multiple of block")
+        q = np.empty((rows, cols), np.int8)
+        ex = np.empty((rows, cols // block), np.uint8)
+        rc = lib.mxo_quantize(_ptr(x), rows, cols, cols, block, e, w, rounding, _ptr(q), _ptr(ex))
+    else:
+        if block < 1 or rows % block:
+            raise ValueError("rows must be a multiple of block")
+        q = np.empty((cols, rows), np.int8)
+        ex = np.empty((cols, rows // block), np.uint8)
+        rc = lib.mxo_quantize_axis0(_ptr(x), rows, cols, cols, block, e, w, rounding, _ptr(q), _ptr(ex))
+    _check(rc, "quantize")
+    return q, ex
+
+
+def dequantize(q: np.ndarray, exps: np.ndarray, block: int, w: int, e: int = 8) -> np.ndarray:
+    """Exact values of an MXInt tensor, as float64 [rows, cols]."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    exps = np.ascontiguousarray(exps, dtype=np.uint8)
+    rows, cols = q.shape
+    assert exps.shape == (rows, cols // block)
+    y = np.empty((rows, cols), np.float64)
+    _check(_load().mxo_dequantize(_ptr(q), _ptr(exps), rows, cols, block, e, w, _ptr(y)), "dequantize")
+    return y
+
+
+def pack_bits(q: np.ndarray, w: int) -> np.ndarray:
+    """Signed mantissas int8 [rows, cols] -> uint8 [rows, cols*w/8] little-endian bit stream."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    rows, cols = q.shape
+    out = np.empty((rows, cols * w // 8), np.uint8)
+    _check(_load().mxo_pack_bits(_ptr(q), rows, cols, w, _ptr(out)), "pack_bits")
+    return out
+
+
+def unpack_bits(packed: np.ndarray, cols: int, w: int) -> np.ndarray:
+    """Inverse of pack_bits."""
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    rows = packed.shape[0]
+    assert packed.shape[1] == cols * w // 8
+    q = np.empty((rows, cols), np.int8)
+    _check(_load().mxo_unpack_bits(_ptr(packed), rows, cols, w, _ptr(q)), "unpack_bits")
+    return q
+
+
+def gemm(qa: np.ndarray, ea: np.ndarray, wa: int, qb: np.ndarray, eb: np.ndarray, wb: int,
+         block: int, e: int = 8, rows: Optional[Tuple[int, int]] = None,
+         want_mag: bool = False):
+    """Y[m,n] = sum over K-blocks of (exact integer block dot) * 2^(sum of the two block exponents).
+
+    qa [M,K], ea [M,K/block]; qb [N,K] (the right operand stored row-per-output-column), eb [N,K/block].
+    Returns float64 [M,N] (rows outside ``rows=(begin,end)`` are left as NaN), and with
+    want_mag also sum_b |term_b|.
+    """
+    qa = np.ascontiguousarray(qa, dtype=np.int8)
+    qb = np.ascontiguousarray(qb, dtype=np.int8)
+    ea = np.ascontiguousarray(ea, dtype=np.uint8)
+    eb = np.ascontiguousarray(eb, dtype=np.uint8)
+    M, K = qa.shape
+    N, K2 = qb.shape
+    assert K == K2 and ea.shape == (M, K // block) and eb.shape == (N, K // block)
+    m0, m1 = (0, M) if rows is None else rows
+    y = np.full((M, N), np.nan, np.float64)
+    mag = np.full((M, N), np.nan, np.float64) if want_mag else None
+    rc = _load().mxo_gemm(_ptr(qa), _ptr(ea), wa, _ptr(qb), _ptr(eb), wb, M, N, K, block, e, m0, m1,
+                          _ptr(y), _ptr(mag) if want_mag else None)
+    _check(rc, "gemm")
+    return (y, mag) if want_mag else y
+
+
+def linear(x: np.ndarray, wt: np.ndarray, block: int, wx: int, ww: int, e: int = 8,
+           rounding: int = RNE, want_mag: bool = False):
+    """Quantize x [M,K] and wt [N,K] along K, then the MXInt product: the emulated linear layer
+    of Section 3.2 without output re-quantization."""
+    qa, ea = quantize(x, block, wx, e, rounding)
+    qb, eb = quantize(wt, block, ww, e, rounding)
+    return gemm(qa, ea, wx, qb, eb, ww, block, e, want_mag=want_mag)

@@ -1,0 +1,385 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something other than
+itself -- values the paper prints, hand-worked blocks, exact rational brute force, closed forms,
+invariants and library routines.  No GPU, no GPU library.
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import mx_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                yield [c.strip() for c in line.split("|")]
+
+
+# ----------------------------------------------------------------------------------------------
+# Size accounting: the numbers the paper prints (Section 4.1 Eq. 1; Table 1)
+# ----------------------------------------------------------------------------------------------
+def test_paper_printed_sizes():
+    rows = {r[0]: r for r in _rows("paper_values.txt")}
+    _, B, e, m, printed, _ = rows["avg_bits_MXInt_16x2_8_7"]
+    B, e, m = int(B), int(e), int(m)
+    w = m + 1                                   # stored width = mantissa + sign (Eq. 1)
+    x = np.zeros((3, 4 * B), np.float32)
+    q, ex = orc.quantize(x, B, w, e)
+    nbytes = orc.pack_bits(q, w).nbytes + ex.nbytes
+    assert Fraction(8 * nbytes, x.size) == Fraction(printed)          # 8.25 bits per element
+    _, B, e, m, printed, _ = rows["mem_density_MXInt8_vs_FP32"]
+    bits = Fraction(int(e), int(B)) + int(m) + 1
+    assert math.floor(10 * Fraction(32) / bits) / 10 == float(printed)  # 32/8.25 = 3.88 -> "3.8x"
+
+
+# ----------------------------------------------------------------------------------------------
+# Hand-worked blocks
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("row", list(_rows("handworked_blocks.txt")))
+def test_handworked_blocks(row):
+    w, rnd, xs, ebyte, qs, hexbytes = row
+    w = int(w)
+    x = np.array([[float(v) for v in xs.split()]], np.float32)
+    q, ex = orc.quantize(x, x.shape[1], w, 8, orc.RNE if rnd == "rne" else orc.RTZ)
+    assert ex.tolist() == [[int(ebyte)]]
+    assert q.tolist() == [[int(v) for v in qs.split()]]
+    if hexbytes != "-":
+        assert orc.pack_bits(q, w).tolist() == [[int(h, 16) for h in hexbytes.split()]]
+
+
+@pytest.mark.parametrize("row", list(_rows("handworked_gemm.txt")))
+def test_handworked_gemm(row):
+    qa, ea, wa, qb, eb, wb, val = row
+    qa = np.array([[int(v) for v in qa.split()]], np.int8)
+    qb = np.array([[int(v) for v in qb.split()]], np.int8)
+    y = orc.gemm(qa, np.array([[int(ea)]], np.uint8), int(wa), qb, np.array([[int(eb)]], np.uint8),
+                 int(wb), qa.shape[1])
+    assert y[0, 0] == float(val)
+
+
+# ----------------------------------------------------------------------------------------------
+# Brute force with exact rationals: nearest representable value, ties to even, symmetric clamp
+# ----------------------------------------------------------------------------------------------
+def _brute_block(xs, w, e, rounding):
+    """Definition only: E is the integer with 2^E <= max|x| < 2^(E+1) (found by search, clamped to the
+    e-bit range); each q is the integer in [-qmax, qmax] nearest to x / 2^(E-(w-2))."""
+    fx = [Fraction(float(v)) for v in xs]
+    amax = max(abs(v) for v in fx)
+    bias = 2 ** (e - 1) - 1
+    qmax = 2 ** (w - 1) - 1
+    if amax == 0:
+        return 0, [0] * len(fx)
+    E = -200
+    while Fraction(2) ** (E + 1) <= amax:
+        E += 1
+    assert Fraction(2) ** E <= amax < Fraction(2) ** (E + 1)
+    E = min(max(E, -bias), 2 ** e - 1 - bias)
+    unit = Fraction(2) ** (E - (w - 2))
+    qs = []
+    for v in fx:
+        t = v / unit
+        if rounding == orc.RNE:
+            best = None
+            for cand in range(-qmax, qmax + 1):
+                d = abs(t - cand)
+                if best is None or d < best[0] or (d == best[0] and cand % 2 == 0 and best[1] % 2 != 0):
+                    best = (d, cand)
+            qs.append(best[1])
+        else:
+            cand = int(abs(t))                      # floor of the magnitude
+            cand = min(cand, qmax)
+            qs.append(cand if t >= 0 else -cand)
+    return E + bias, qs
+
+
+@pytest.mark.parametrize("w", [2, 3, 4, 5, 8])
+@pytest.mark.parametrize("rounding", [orc.RNE, orc.RTZ])
+def test_bruteforce_tiny_blocks(w, rounding):
+    rng = np.random.default_rng(100 + w)
+    for B in (1, 2, 3, 4):
+        for trial in range(60):
+            scale = 2.0 ** rng.integers(-20, 20)
+            x = (rng.standard_normal(B) * scale).astype(np.float32)
+            if trial % 5 == 0:                       # plant exact half-way points and a saturating max
+                E = math.floor(math.log2(float(np.abs(x).max()) or 1.0))
+                unit = 2.0 ** (E - (w - 2))
+                x[0] = np.float32((rng.integers(0, 2 ** (w - 1)) + 0.5) * unit * rng.choice([-1, 1]))
+            eb, qs = _brute_block(x, w, 8, rounding)
+            q, ex = orc.quantize(x[None, :], B, w, 8, rounding)
+            assert ex[0, 0] == eb and q[0].tolist() == qs, (x, w, rounding)
+
+
+def test_halfway_points_dense():
+    """Every half-way point (j + 1/2) units, both signs, for every width: ties go to the even code."""
+    for w in range(2, 9):
+        qmax = 2 ** (w - 1) - 1
+        anchor = float(2 ** (w - 2)) if w > 2 else 1.0      # keeps E = w-2, i.e. unit = 1
+        for j in range(0, qmax + 1):
+            for sgn in (1.0, -1.0):
+                x = np.array([[anchor, sgn * (j + 0.5)]], np.float32)
+                if abs(x[0, 1]) >= 2 * anchor:
+                    continue                                 # would move the exponent
+                q, ex = orc.quantize(x, 2, w)
+                assert ex[0, 0] == 127 + (w - 2)
+                lo, hi = j, j + 1
+                want = lo if lo % 2 == 0 else hi
+                want = min(want, qmax)
+                assert q[0, 1] == int(sgn) * want, (w, j, sgn)
+                qz, _ = orc.quantize(x, 2, w, rounding=orc.RTZ)
+                assert qz[0, 1] == int(sgn) * j
+
+
+# ----------------------------------------------------------------------------------------------
+# Exponent rule: closed form and invariants
+# ----------------------------------------------------------------------------------------------
+def test_exponent_is_floor_log2_of_block_max():
+    rng = np.random.default_rng(7)
+    x = (rng.standard_normal((64, 256)) * np.exp(rng.uniform(-30, 30, (64, 1)))).astype(np.float32)
+    for B in (8, 16, 32):
+        q, ex = orc.quantize(x, B, 6)
+        amax = np.abs(x.astype(np.float64)).reshape(64, -1, B).max(-1)
+        E = ex.astype(np.int64) - 127
+        assert np.all(np.ldexp(1.0, E) <= amax) and np.all(amax < np.ldexp(1.0, E + 1))
+        # the max-magnitude element sets the exponent: its mantissa is in the top binade
+        qm = np.abs(q.astype(np.int64)).reshape(64, -1, B).max(-1)
+        assert np.all(qm >= 2 ** (6 - 2)) and np.all(qm <= 2 ** 5 - 1)
+
+
+def test_power_of_two_scaling_shifts_only_the_exponent():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((8, 128)).astype(np.float32)
+    q0, e0 = orc.quantize(x, 16, 5)
+    for j in (-40, -3, 1, 17, 60):
+        q1, e1 = orc.quantize(np.ldexp(x, j).astype(np.float32), 16, 5)
+        assert np.array_equal(q0, q1)
+        assert np.array_equal(e0.astype(int) + j, e1.astype(int))
+
+
+def test_error_bound_and_sign():
+    rng = np.random.default_rng(9)
+    x = rng.standard_t(3, size=(32, 512)).astype(np.float32)
+    for w in (3, 4, 6, 8):
+        for rounding in (orc.RNE, orc.RTZ):
+            q, ex = orc.quantize(x, 32, w, rounding=rounding)
+            xh = orc.dequantize(q, ex, 32, w)
+            unit = np.repeat(np.ldexp(1.0, ex.astype(int) - 127 - (w - 2)), 32, axis=1)
+            err = np.abs(x.astype(np.float64) - xh)
+            clamped = np.abs(q) == 2 ** (w - 1) - 1
+            if rounding == orc.RNE:
+                assert np.all(err[~clamped] <= unit[~clamped] / 2)
+            else:
+                assert np.all(err[~clamped] < unit[~clamped])
+                assert np.all(np.abs(xh) <= np.abs(x))          # toward zero never grows a value
+            assert np.all(err[clamped] <= unit[clamped])
+            assert np.all((np.sign(xh) == np.sign(x)) | (xh == 0))
+            assert np.abs(q).max() <= 2 ** (w - 1) - 1            # the code -2^(w-1) is never produced
+
+
+def test_roundtrip_and_idempotence():
+    rng = np.random.default_rng(10)
+    for w in range(2, 9):
+        qmax = 2 ** (w - 1) - 1
+        q = rng.integers(-qmax, qmax + 1, size=(16, 64)).astype(np.int8)
+        q[:, ::16] = 2 ** (w - 2)                        # normalised: each block has a top-binade code
+        ex = rng.integers(40, 200, size=(16, 4)).astype(np.uint8)
+        xh = orc.dequantize(q, ex, 16, w)
+        assert np.array_equal(xh, xh.astype(np.float32).astype(np.float64))   # exactly fp32 values
+        q2, ex2 = orc.quantize(xh.astype(np.float32), 16, w)
+        assert np.array_equal(q, q2) and np.array_equal(ex, ex2)
+    x = rng.standard_normal((16, 64)).astype(np.float32)
+    q, ex = orc.quantize(x, 16, 4)
+    q2, ex2 = orc.quantize(orc.dequantize(q, ex, 16, 4).astype(np.float32), 16, 4)
+    assert np.array_equal(q, q2) and np.array_equal(ex, ex2)
+
+
+def test_widening_cast_is_value_exact():
+    """Section 4 (mixed precision): a cast to a wider mantissa only extends bits."""
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((8, 64)).astype(np.float32)
+    q4, e4 = orc.quantize(x, 16, 4)
+    v = orc.dequantize(q4, e4, 16, 4).astype(np.float32)
+    q7, e7 = orc.quantize(v, 16, 7)
+    assert np.array_equal(e4, e7)
+    assert np.array_equal(q7.astype(int), q4.astype(int) * 8)
+
+
+def test_zero_subnormal_and_clamped_exponents():
+    x = np.zeros((1, 16), np.float32)
+    q, ex = orc.quantize(x, 16, 8)
+    assert ex[0, 0] == 0 and not q.any()
+    # fp32 subnormals count with their true value; E clamps at -127 (byte 0)
+    tiny = np.float32(2.0 ** -140)
+    x[0, 3] = tiny
+    q, ex = orc.quantize(x, 16, 8)
+    assert ex[0, 0] == 0                       # floor(log2) = -140 clamps to -127
+    assert q[0, 3] == 0                        # 2^-140 / 2^(-127-6) = 2^-7 rounds to 0
+    x[0, 3] = np.float32(2.0 ** -127)          # subnormal in fp32, exactly representable
+    q, ex = orc.quantize(x, 16, 8)
+    assert ex[0, 0] == 0 and q[0, 3] == 64
+    # a narrow exponent (e = 4: bias 7, E in [-7, 8]) saturates large blocks and flushes small ones
+    big = np.array([[1000.0, 3.0]], np.float32)
+    q, ex = orc.quantize(big, 2, 4, e=4)
+    assert ex[0, 0] == 15 and q.tolist() == [[7, 0]]      # unit 2^(8-2)=64: 1000/64=15.6 -> 7 ; 3/64 -> 0
+    small = np.array([[2.0 ** -9, 2.0 ** -12]], np.float32)
+    q, ex = orc.quantize(small, 2, 4, e=4)
+    assert ex[0, 0] == 0 and q.tolist() == [[1, 0]]       # E=-7, unit 2^-9
+
+
+def test_nonfinite_inputs_raise():
+    x = np.ones((1, 16), np.float32)
+    x[0, 5] = np.inf
+    with pytest.raises(ValueError):
+        orc.quantize(x, 16, 8)
+    x[0, 5] = np.nan
+    with pytest.raises(ValueError):
+        orc.quantize(x, 16, 8)
+
+
+def test_axis0_is_blocks_down_columns():
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((32, 5)).astype(np.float32)
+    q, ex = orc.quantize(x, 16, 5, axis=0)
+    assert q.shape == (5, 32) and ex.shape == (5, 2)
+    for c in range(5):
+        for b in range(2):
+            eb, qs = _brute_block(x[16 * b:16 * b + 16, c], 5, 8, orc.RNE)
+            assert ex[c, b] == eb and q[c, 16 * b:16 * b + 16].tolist() == qs
+
+
+# ----------------------------------------------------------------------------------------------
+# Bit packing: against numpy's own bit routines
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("w", range(2, 9))
+def test_pack_bits_against_numpy_bitorder_little(w):
+    rng = np.random.default_rng(20 + w)
+    q = rng.integers(-(2 ** (w - 1)), 2 ** (w - 1), size=(5, 64)).astype(np.int8)
+    codes = (q.astype(np.int64) & (2 ** w - 1)).astype(np.uint8)
+    bits = ((codes[:, :, None] >> np.arange(w)) & 1).astype(np.uint8).reshape(5, -1)
+    want = np.packbits(bits, axis=1, bitorder="little")
+    got = orc.pack_bits(q, w)
+    assert np.array_equal(got, want)
+    assert np.array_equal(orc.unpack_bits(got, 64, w), q)
+
+
+# ----------------------------------------------------------------------------------------------
+# Dequantize: against 2.0**k arithmetic in exact rationals
+# ----------------------------------------------------------------------------------------------
+def test_dequantize_exact():
+    rng = np.random.default_rng(30)
+    for w in (2, 4, 8):
+        q = rng.integers(-(2 ** (w - 1)) + 1, 2 ** (w - 1), size=(3, 32)).astype(np.int8)
+        ex = rng.integers(0, 256, size=(3, 2)).astype(np.uint8)
+        y = orc.dequantize(q, ex, 16, w)
+        for r in range(3):
+            for c in range(32):
+                want = Fraction(int(q[r, c])) * Fraction(2) ** (int(ex[r, c // 16]) - 127 - (w - 2))
+                assert Fraction(y[r, c]) == want
+
+
+# ----------------------------------------------------------------------------------------------
+# GEMM
+# ----------------------------------------------------------------------------------------------
+def _rand_mx(rng, rows, K, block, w, elo=100, ehi=140):
+    qmax = 2 ** (w - 1) - 1
+    q = rng.integers(-qmax, qmax + 1, size=(rows, K)).astype(np.int8)
+    ex = rng.integers(elo, ehi, size=(rows, K // block)).astype(np.uint8)
+    return q, ex
+
+
+def test_gemm_exact_rational_tiny():
+    rng = np.random.default_rng(40)
+    M, N, K = 3, 4, 16
+    for (wa, wb, block) in [(8, 4, 4), (3, 7, 2), (2, 2, 8)]:
+        for (elo, ehi) in [(120, 132), (60, 200)]:
+            qa, ea = _rand_mx(rng, M, K, block, wa, elo, ehi)
+            qb, eb = _rand_mx(rng, N, K, block, wb, elo, ehi)
+            y, mag = orc.gemm(qa, ea, wa, qb, eb, wb, block, want_mag=True)
+            for m in range(M):
+                for n in range(N):
+                    tot = Fraction(0)
+                    tmag = Fraction(0)
+                    for b in range(K // block):
+                        d = sum(int(qa[m, k]) * int(qb[n, k]) for k in range(b * block, (b + 1) * block))
+                        s = int(ea[m, b]) - 127 - (wa - 2) + int(eb[n, b]) - 127 - (wb - 2)
+                        tot += d * Fraction(2) ** s
+                        tmag += abs(d) * Fraction(2) ** s
+                    if ehi - elo < 20:
+                        # few terms, narrow exponent spread: the double sums are exact
+                        assert Fraction(y[m, n]) == tot
+                        assert Fraction(mag[m, n]) == tmag
+                    else:
+                        # wide spread: each of the K/block - 1 double additions rounds once
+                        assert abs(Fraction(y[m, n]) - tot) <= (K // block) * Fraction(2) ** -53 * tmag
+
+
+def test_gemm_equals_float_matmul_of_dequantized_operands():
+    """Section 3.2: the emulated operator is the float operator applied to the dequantized inputs."""
+    rng = np.random.default_rng(41)
+    M, N, K, block = 24, 40, 256, 16
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[:, 7] *= 50
+    wt = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    for wa, wb in [(8, 4), (6, 4), (2, 8)]:
+        qa, ea = orc.quantize(x, block, wa)
+        qb, eb = orc.quantize(wt, block, wb)
+        y, mag = orc.gemm(qa, ea, wa, qb, eb, wb, block, want_mag=True)
+        ref = orc.dequantize(qa, ea, block, wa) @ orc.dequantize(qb, eb, block, wb).T   # numpy float64 matmul
+        assert np.all(np.abs(y - ref) <= 1e-13 * mag)
+        assert np.all(mag >= np.abs(y) * (1 - 1e-12))
+
+
+def test_gemm_special_cases():
+    rng = np.random.default_rng(42)
+    M, K, block, wa = 6, 64, 16, 7
+    qa, ea = _rand_mx(rng, M, K, block, wa)
+    # identity weights: value 1.0 = code 2^(w-2) with E = 0  ->  output equals the dequantized activations
+    wb = 4
+    qb = (np.eye(K, dtype=np.int8) * 2 ** (wb - 2)).astype(np.int8)
+    eb = np.full((K, K // block), 127, np.uint8)
+    y = orc.gemm(qa, ea, wa, qb, eb, wb, block)
+    assert np.array_equal(y, orc.dequantize(qa, ea, block, wa))
+    # all exponents equal: one integer matrix product times one power of two
+    qb, _ = _rand_mx(rng, 5, K, block, wb)
+    ea2 = np.full_like(ea, 130)
+    eb2 = np.full((5, K // block), 120, np.uint8)
+    y = orc.gemm(qa, ea2, wa, qb, eb2, wb, block)
+    want = (qa.astype(np.int64) @ qb.astype(np.int64).T) * 2.0 ** ((130 - 127 - 5) + (120 - 127 - 2))
+    assert np.array_equal(y, want)
+    # one block per row (block = K): per-row times per-column scaling of the integer product
+    ea3 = rng.integers(110, 140, size=(M, 1)).astype(np.uint8)
+    eb3 = rng.integers(110, 140, size=(5, 1)).astype(np.uint8)
+    y = orc.gemm(qa, ea3, wa, qb, eb3, wb, K)
+    want = (qa.astype(np.int64) @ qb.astype(np.int64).T) * np.ldexp(1.0, ea3.astype(int) - 132) \
+        * np.ldexp(1.0, eb3.astype(int).T - 129)
+    assert np.array_equal(y, want)
+    # transposing the roles of the operands transposes the result
+    y_t = orc.gemm(qb, eb3, wb, qa, ea3, wa, K)
+    assert np.array_equal(y_t, y.T)
+
+
+def test_gemm_row_window():
+    rng = np.random.default_rng(43)
+    qa, ea = _rand_mx(rng, 10, 32, 16, 8)
+    qb, eb = _rand_mx(rng, 7, 32, 16, 4)
+    full = orc.gemm(qa, ea, 8, qb, eb, 4, 16)
+    part = orc.gemm(qa, ea, 8, qb, eb, 4, 16, rows=(3, 6))
+    assert np.array_equal(part[3:6], full[3:6]) and np.isnan(part[:3]).all() and np.isnan(part[6:]).all()
+
+
+def test_linear_matches_float_linear_within_quantization_error():
+    """Sanity of the whole chain on config-1-shaped data: the MXInt linear tracks the fp64 linear to
+    the accuracy the formats allow (8-bit activations, 4-bit weights)."""
+    from paper_2307_15517_amd import inputs
+    case = inputs.single_linear()[0]
+    x, wt = inputs.make(case)
+    y = orc.linear(x, wt, case.block, case.wx, case.ww)
+    ref = x.astype(np.float64) @ wt.astype(np.float64).T
+    rel = np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    assert 0.01 < rel < 0.2            # 4-bit weights: ~10 % error; not zero, not garbage
