@@ -1,0 +1,162 @@
+/*
+ * mx.h -- C ABI of the MXInt library for MI355X (gfx950).
+ *
+ * MXInt is the block floating-point format of the paper "A Dataflow Compiler for
+ * Efficient LLM Inference using Custom Microscaling Formats": a block of elements
+ * shares one exponent, every element keeps its own signed integer mantissa
+ * (Section 2, "What are MX Formats?"; Section 4.1, the 3-tuple (B, e, m) and Eq. 1).
+ * This library holds the data-parallel part of inference in that format: the block
+ * quantizer, its inverse, a re-layout of quantized operands for the matrix cores,
+ * and the MXInt x MXInt matrix product (Section 3.2: integer mantissa products and
+ * sums, the two shared exponents applied once per block).
+ *
+ * Conventions for every entry point
+ *   - Pointers named x, y, Y, mant, exps, packed, A_packed, B_packed are DEVICE
+ *     pointers (e.g. a torch tensor's data_ptr()).  The library allocates nothing,
+ *     frees nothing, keeps no state between calls, and never synchronizes: all work
+ *     is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *   - The return value is an mx_status.  Nothing throws or aborts across this
+ *     boundary.  MX_ERR_BAD_ARG: a null pointer, a negative size, a size that is not
+ *     a whole number of blocks, a format outside the ranges stated at mx_format, or
+ *     a misaligned pointer.  MX_ERR_UNSUPPORTED: a legal request this build has no
+ *     kernel for.  MX_ERR_DEVICE: the HIP runtime refused the launch.
+ *   - Inputs must be finite; NaN and infinity give unspecified mantissas (no fault).
+ *
+ * Canonical form of a quantized tensor of `rows` rows and `cols` columns with the
+ * blocks running along the columns (this is the form bit-exactness is stated on):
+ *   mant: rows * (cols*w/8) bytes.  Element k of a row occupies bits [k*w, (k+1)*w)
+ *         of that row's bit stream; bit i of the stream is bit (i mod 8) of byte
+ *         (i div 8); mantissas are w-bit two's complement.
+ *   exps: rows * (cols/block) bytes, one per block: E + (2^(e-1) - 1).
+ *   A batch is `batch` such tensors back to back.
+ * The value of an element is  q * 2^(E - (w - 2)).
+ */
+#ifndef MX_H_
+#define MX_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MX_API __attribute__((visibility("default")))
+
+/*
+ * One MXInt format (Section 4.1).  The paper writes MXInt(B, e, m) with m the
+ * mantissa width WITHOUT the sign bit (Eq. 1: p = e/prod(B) + m + 1); here
+ * mant_bits = m + 1 is the stored width of an element, so the paper's
+ * MXInt((16,2), 8, 7) has block = 32, exp_bits = 8, mant_bits = 8.
+ */
+typedef struct {
+    int32_t block;     /* elements sharing one exponent, consecutive along the reduction axis:
+                          8, 16, 32 or 64 for mx_quantize / mx_dequantize;
+                          16, 32 or 64 for mx_pack / mx_unpack / mx_gemm / mx_linear */
+    int32_t exp_bits;  /* e, 2..8 (the paper fixes 8 for every tensor, Section 4.1) */
+    int32_t mant_bits; /* w = m + 1, 2..8; mantissas lie in -(2^(w-1)-1) .. +(2^(w-1)-1) */
+    int32_t rounding;  /* MX_RNE or MX_RTZ */
+} mx_format;
+
+enum { MX_RNE = 0,  /* round to nearest, ties to the even mantissa */
+       MX_RTZ = 1   /* round toward zero (the "truncation" of a width cast, Section 4) */ };
+
+typedef enum { MX_OK = 0, MX_ERR_BAD_ARG = 1, MX_ERR_UNSUPPORTED = 2, MX_ERR_DEVICE = 3 } mx_status;
+
+/*
+ * Device layouts mx_pack can write.  The bytes are opaque to the caller;
+ * mx_unpack restores the canonical form bit for bit.
+ *   MX_LAYOUT_FRAGMENT: w bits per element + 1 byte per block, i.e. exactly the
+ *       density of the canonical form (Eq. 1), arranged in the order the matrix
+ *       cores' lanes consume it.  Rows are padded to a multiple of 32 and columns to
+ *       a multiple of 4 blocks with zeros.  Either operand of mx_gemm, any M.
+ */
+enum { MX_LAYOUT_FRAGMENT = 0 };
+
+/* Library version: major*10000 + minor*100 + patch. */
+MX_API int32_t mx_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+MX_API const char* mx_status_string(mx_status s);
+
+/* Bytes of the canonical mantissa / exponent arrays of batch x rows x cols; 0 on a bad format. */
+MX_API size_t mx_mant_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f);
+MX_API size_t mx_exps_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f);
+
+/*
+ * Block quantizer (Section 3.2 "quantize ... between the given format and
+ * floating-point numbers"; format of Section 4.1).  Per block of f.block elements:
+ *   E = floor(log2(max |x|)) clamped to the e-bit range [-(2^(e-1)-1), 2^(e-1)]; a zero
+ *   block stores exponent byte 0;  q = round(x * 2^-(E-(w-2))) with f.rounding, then
+ *   clamped to +-(2^(w-1)-1).  fp32 subnormals count with their true value.
+ *
+ * x: batch matrices of rows x cols floats; element (b, r, c) at x[b*batch_stride +
+ *    r*row_stride + c] (strides in elements; the columns are contiguous).
+ * axis = 1: blocks run along the columns; cols % block == 0.
+ *           mant, exps receive the canonical form of batch x rows x cols.
+ * axis = 0: blocks run down the rows of each column; rows % block == 0.
+ *           mant, exps receive the canonical form of the TRANSPOSED matrices,
+ *           batch x cols x rows (the layout the right operand of a product needs
+ *           when the reduction runs over the rows of x).
+ * x must be 4-byte aligned; row_stride >= cols; mant and exps are written densely.
+ */
+MX_API mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                      int64_t batch_stride, int32_t axis, mx_format f, uint8_t* mant, uint8_t* exps,
+                      void* stream);
+
+/*
+ * Inverse of the quantizer's encoding (Section 3.2 "dequantize"): y[b][r][c] =
+ * q * 2^(E - (w-2)) as fp32, dense batch x rows x cols, from the canonical form of
+ * batch x rows x cols (blocks along the columns).  Exact whenever the value is
+ * representable in fp32 (always, except below the fp32 subnormal spacing).
+ */
+MX_API mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows,
+                        int64_t cols, mx_format f, float* y, void* stream);
+
+/* Bytes mx_pack writes for batch x rows x cols in `layout`; 0 on a bad argument. */
+MX_API size_t mx_packed_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f, int32_t layout);
+
+/*
+ * Canonical form -> device layout (the format's memory density is the point of
+ * Table 1 and Eq. 1; the layouts keep it).  rows x cols is the operand as mx_gemm
+ * sees it: rows = M (left operand) or N (right operand), cols = K, blocks along K.
+ * `packed` must be 256-byte aligned and hold mx_packed_bytes(...) bytes.
+ */
+MX_API mx_status mx_pack(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
+                  mx_format f, int32_t layout, void* packed, void* stream);
+
+/* Exact inverse of mx_pack. */
+MX_API mx_status mx_unpack(const void* packed, int64_t batch, int64_t rows, int64_t cols, mx_format f,
+                    int32_t layout, uint8_t* mant, uint8_t* exps, void* stream);
+
+/*
+ * MXInt x MXInt product (Section 3.2, the MXInt dot-product operator):
+ *   Y[b][m][n] = sum over K-blocks j of
+ *        ( sum_{k in block j} qa[m][k] * qb[n][k] )  *  2^(Ea[m][j] + Eb[n][j] - (wa-2) - (wb-2))
+ * The inner sum is exact integer arithmetic on the matrix cores; each block's
+ * scaled value is added into an fp32 accumulator.  Both operands come from mx_pack
+ * in the same layout.  The left operand is M x K; the right operand is given as
+ * N x K (one row per output column, like torch.nn.Linear.weight).
+ * fa.block == fb.block and fa.exp_bits == fb.exp_bits are required.
+ * Y: fp32, element (b, m, n) at Y[b*batch_stride_y + m*ldy + n]; ldy >= N.
+ * M <= 8 takes the bandwidth-bound decode path (one pass over the right operand).
+ */
+MX_API mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed, mx_format fa,
+                  const void* B_packed, mx_format fb, int32_t layout, float* Y, int64_t ldy,
+                  int64_t batch_stride_y, void* stream);
+
+/*
+ * Linear layer on fp32 activations for decode (M <= 8): quantizes x [M x K] with fx
+ * on the fly (same arithmetic as mx_quantize, axis 1), then the product above
+ * against B_packed [N x K].  The result equals mx_quantize + mx_pack + mx_gemm.
+ * A_scratch: device buffer of mx_packed_bytes(1, M, K, fx, layout) bytes, 256-byte
+ * aligned, that receives the packed activations (caller-owned, may be reused).
+ */
+MX_API mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
+                    void* A_scratch, const void* B_packed, int64_t N, mx_format fb, int32_t layout,
+                    float* Y, int64_t ldy, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MX_H_ */

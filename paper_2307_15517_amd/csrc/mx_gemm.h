@@ -1,0 +1,24 @@
+// Arguments shared by the product kernels and their host dispatch.
+#pragma once
+#include "mx_common.h"
+
+namespace mx {
+
+struct GemmArgs {
+    const uint8_t* A;
+    const uint8_t* B;
+    float* Y;
+    int64_t M, N;
+    int64_t groupsA, groupsB, chunks;
+    int64_t matrixA, matrixB;     // packed bytes per batch entry
+    int64_t ldy, batch_stride_y;
+    int32_t recordA, recordB;
+    int32_t eadj;                 // -2*bias - (wa-2) - (wb-2)
+};
+
+// One instance per block size, each compiled in its own translation unit.
+mx_status gemm_block16(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st);
+mx_status gemm_block32(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st);
+mx_status gemm_block64(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st);
+
+}  // namespace mx

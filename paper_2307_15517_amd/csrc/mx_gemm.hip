@@ -1,0 +1,39 @@
+// Host entry point of the MXInt x MXInt product: argument checks and dispatch on the block size.
+#include "mx_gemm.h"
+
+using namespace mx;
+
+extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed,
+                             mx_format fa, const void* B_packed, mx_format fb, int32_t layout, float* Y,
+                             int64_t ldy, int64_t batch_stride_y, void* stream) {
+    if (!format_ok_quant(fa) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
+    if (fa.block != fb.block || fa.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
+    if (!format_ok_gemm(fa)) return MX_ERR_UNSUPPORTED;
+    if (layout != MX_LAYOUT_FRAGMENT) return MX_ERR_BAD_ARG;
+    if (batch < 0 || M < 0 || N < 0 || K < 0 || K % fa.block != 0 || ldy < N) return MX_ERR_BAD_ARG;
+    if (batch > 1 && batch_stride_y < (M - 1) * ldy + N) return MX_ERR_BAD_ARG;
+    if (batch == 0 || M == 0 || N == 0) return MX_OK;
+    if (!Y || ((uintptr_t)Y & 3)) return MX_ERR_BAD_ARG;
+    if (K > 0 && (!A_packed || !B_packed)) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)A_packed & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
+    if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    const FragGeom ga = frag_geom(M, K, fa.block, fa.mant_bits);
+    const FragGeom gb = frag_geom(N, K, fb.block, fb.mant_bits);
+    if (ceil_div(ga.groups, 4) > 65535) return MX_ERR_UNSUPPORTED;
+    GemmArgs g;
+    g.A = (const uint8_t*)A_packed; g.B = (const uint8_t*)B_packed; g.Y = Y;
+    g.M = M; g.N = N;
+    g.groupsA = ga.groups; g.groupsB = gb.groups; g.chunks = ga.chunks;
+    g.matrixA = ga.matrix; g.matrixB = gb.matrix;
+    g.ldy = ldy; g.batch_stride_y = batch_stride_y;
+    g.recordA = ga.record; g.recordB = gb.record;
+    const int bias = (1 << (fa.exp_bits - 1)) - 1;
+    g.eadj = -2 * bias - (fa.mant_bits - 2) - (fb.mant_bits - 2);
+    hipStream_t st = (hipStream_t)stream;
+    switch (fa.block) {
+        case 16: return gemm_block16(g, fa.mant_bits, fb.mant_bits, batch, st);
+        case 32: return gemm_block32(g, fa.mant_bits, fb.mant_bits, batch, st);
+        case 64: return gemm_block64(g, fa.mant_bits, fb.mant_bits, batch, st);
+    }
+    return MX_ERR_UNSUPPORTED;
+}

@@ -1,0 +1,291 @@
+// MXInt x MXInt product on the integer matrix cores of gfx950, operands in the fragment layout.
+//
+// Arithmetic (Section 3.2 of the paper, the MXInt dot-product operator): per K-block the mantissa
+// products are summed exactly in int32 by one MFMA whose K extent equals the block (32x32x16 for
+// block 16, 32x32x32 for block 32, two chained 32x32x32 for block 64); the block's value is that
+// integer times 2^(Ea + Eb - (wa-2) - (wb-2)), applied with v_ldexp_f32 and added into an fp32
+// accumulator.  The left operand feeds the MFMA "A" side, so in the 32x32 result a lane owns one
+// output column n and its 16 registers are 16 rows m: the right operand's block exponent is one
+// value per lane, the left operand's is one value per register.
+#include "mx_gemm.h"
+
+#ifndef MX_GEMM_BLOCK
+#error "compile with -DMX_GEMM_BLOCK=16, 32 or 64"
+#endif
+
+namespace mx {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+
+// dwords of one lane piece
+template <int W, int B> struct Piece { static constexpr int kDw = B * W / 16; };
+
+template <int NDW>
+__device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t* out) {
+    if constexpr (NDW % 4 == 0) {
+#pragma unroll
+        for (int d = 0; d < NDW / 4; ++d) {
+            uint4 v = reinterpret_cast<const uint4*>(p)[d];
+            out[4 * d] = v.x; out[4 * d + 1] = v.y; out[4 * d + 2] = v.z; out[4 * d + 3] = v.w;
+        }
+    } else if constexpr (NDW % 2 == 0) {
+#pragma unroll
+        for (int d = 0; d < NDW / 2; ++d) {
+            uint2 v = reinterpret_cast<const uint2*>(p)[d];
+            out[2 * d] = v.x; out[2 * d + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < NDW; ++d) out[d] = reinterpret_cast<const uint32_t*>(p)[d];
+    }
+}
+
+// Half-block j of a lane piece -> B/2 sign-extended int8 in B/8 dwords.  For W = 4 the bytes come
+// out multiplied by 16 (kScaleLog2 = 4), which the exponent offset takes back.
+template <int W, int B> struct Unpack {
+    static constexpr int kScaleLog2 = (W == 4) ? 4 : 0;
+    __device__ __forceinline__ static void run(const uint32_t* piece, int j, uint32_t* out) {
+        constexpr int kOut = B / 8;
+        if constexpr (W == 8) {
+#pragma unroll
+            for (int d = 0; d < kOut; ++d) out[d] = piece[j * kOut + d];
+        } else if constexpr (W == 4) {
+#pragma unroll
+            for (int d = 0; d < kOut / 2; ++d) {
+                const uint32_t x = piece[j * (kOut / 2) + d];
+                out[2 * d] = (x << 4) & 0xF0F0F0F0u;
+                out[2 * d + 1] = x & 0xF0F0F0F0u;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < kOut; ++d) {
+                uint32_t o = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int bit = (j * (B / 2) + d * 4 + t) * W;
+                    o |= ((uint32_t)stream_get<W>(piece, bit) & 0xFFu) << (8 * t);
+                }
+                out[d] = o;
+            }
+        }
+    }
+};
+
+// Exact int32 dot products of one block: D (32x32) = A_half-blocks x B_half-blocks.
+template <int B>
+__device__ __forceinline__ v16i block_mfma(const uint32_t* a, const uint32_t* b) {
+    v16i z = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    if constexpr (B == 16) {
+        const long la = (long)(((uint64_t)a[1] << 32) | a[0]);
+        const long lb = (long)(((uint64_t)b[1] << 32) | b[0]);
+        return __builtin_amdgcn_mfma_i32_32x32x16_i8(la, lb, z, 0, 0, 0);
+    } else {
+#pragma unroll
+        for (int s = 0; s < B / 32; ++s) {
+            v4i va = {(int)a[4 * s], (int)a[4 * s + 1], (int)a[4 * s + 2], (int)a[4 * s + 3]};
+            v4i vb = {(int)b[4 * s], (int)b[4 * s + 1], (int)b[4 * s + 2], (int)b[4 * s + 3]};
+            z = __builtin_amdgcn_mfma_i32_32x32x32_i8(va, vb, z, 0, 0, 0);
+        }
+        return z;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// General kernel: a workgroup of four waves owns a 128 x 128 tile of Y; each wave a 64 x 64
+// quarter (2 x 2 row groups).  Fragments come straight from global memory in lane order.
+// ------------------------------------------------------------------------------------------------
+template <int WA, int WB, int B>
+__global__ __launch_bounds__(256) void gemm_fragment_kernel(GemmArgs g) {
+    constexpr int kDwA = Piece<WA, B>::kDw, kDwB = Piece<WB, B>::kDw;
+    constexpr int kHalfDw = B / 8;       // int8 dwords per lane per block
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t ga0 = (int64_t)blockIdx.y * 4 + (wave >> 1) * 2;
+    const int64_t gb0 = (int64_t)blockIdx.x * 4 + (wave & 1) * 2;
+    const int64_t bz = blockIdx.z;
+    const uint8_t* Abase = g.A + bz * g.matrixA;
+    const uint8_t* Bbase = g.B + bz * g.matrixB;
+    const int eadj = g.eadj - Unpack<WA, B>::kScaleLog2 - Unpack<WB, B>::kScaleLog2;
+
+    float acc[2][2][16];
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[ta][tb][r] = 0.f;
+
+    for (int64_t c = 0; c < g.chunks; ++c) {
+        uint32_t pa[2][kDwA], pb[2][kDwB];
+        uint32_t ea[2][16];     // [group][4*gq + r]: the four block exponents of row 8*gq + 4*h + r
+        uint32_t eb[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (ga0 + t < g.groupsA) {
+                const uint8_t* rec = Abase + ((ga0 + t) * g.chunks + c) * g.recordA;
+                load_dwords<kDwA>(rec + lane * (kDwA * 4), pa[t]);
+                const uint8_t* ex = rec + 64 * (kDwA * 4);
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) load_dwords<4>(ex + (8 * gq + 4 * h) * 4, &ea[t][4 * gq]);
+            } else {
+#pragma unroll
+                for (int d = 0; d < kDwA; ++d) pa[t][d] = 0;
+#pragma unroll
+                for (int d = 0; d < 16; ++d) ea[t][d] = 0;
+            }
+            if (gb0 + t < g.groupsB) {
+                const uint8_t* rec = Bbase + ((gb0 + t) * g.chunks + c) * g.recordB;
+                load_dwords<kDwB>(rec + lane * (kDwB * 4), pb[t]);
+                eb[t] = reinterpret_cast<const uint32_t*>(rec + 64 * (kDwB * 4))[i];
+            } else {
+#pragma unroll
+                for (int d = 0; d < kDwB; ++d) pb[t][d] = 0;
+                eb[t] = 0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t fa[2][kHalfDw], fb[2][kHalfDw];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                Unpack<WA, B>::run(pa[t], j, fa[t]);
+                Unpack<WB, B>::run(pb[t], j, fb[t]);
+            }
+#pragma unroll
+            for (int ta = 0; ta < 2; ++ta) {
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    const v16i d = block_mfma<B>(fa[ta], fb[tb]);
+                    const int ebj = (int)((eb[tb] >> (8 * j)) & 0xFFu) + eadj;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int e = (int)((ea[ta][r] >> (8 * j)) & 0xFFu) + ebj;
+                        acc[ta][tb][r] += __builtin_ldexpf((float)d[r], e);
+                    }
+                }
+            }
+        }
+    }
+
+    float* Y = g.Y + bz * g.batch_stride_y;
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int64_t n = (gb0 + tb) * 32 + i;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = (ga0 + ta) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                if (m < g.M && n < g.N) Y[m * g.ldy + n] = acc[ta][tb][r];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Decode kernel (M <= 8): bound by one pass over the packed right operand.  A workgroup of NW
+// waves owns 32 output columns; its waves take the K chunks round-robin, each keeping four fp32
+// partial sums per lane (rows 4*h .. 4*h+3), which are added through LDS at the end.
+// ------------------------------------------------------------------------------------------------
+template <int WA, int WB, int B, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_fragment_kernel(GemmArgs g) {
+    constexpr int kDwA = Piece<WA, B>::kDw, kDwB = Piece<WB, B>::kDw;
+    constexpr int kHalfDw = B / 8;
+    __shared__ float red[NW][4][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t gb = blockIdx.x;
+    const int64_t bz = blockIdx.y;
+    const uint8_t* Abase = g.A + bz * g.matrixA;                       // group 0 holds all M <= 8 rows
+    const uint8_t* Bbase = g.B + bz * g.matrixB + gb * g.chunks * g.recordB;
+    const int eadj = g.eadj - Unpack<WA, B>::kScaleLog2 - Unpack<WB, B>::kScaleLog2;
+    const bool arow = i < g.M;
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t c = wave; c < g.chunks; c += NW) {
+        uint32_t pa[kDwA], pb[kDwB], ea[4], eb;
+        const uint8_t* recB = Bbase + c * g.recordB;
+        load_dwords<kDwB>(recB + lane * (kDwB * 4), pb);
+        eb = reinterpret_cast<const uint32_t*>(recB + 64 * (kDwB * 4))[i];
+        const uint8_t* recA = Abase + c * g.recordA;
+        if (arow) {
+            load_dwords<kDwA>(recA + lane * (kDwA * 4), pa);
+        } else {
+#pragma unroll
+            for (int d = 0; d < kDwA; ++d) pa[d] = 0;
+        }
+        load_dwords<4>(recA + 64 * (kDwA * 4) + (4 * h) * 4, ea);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t fa[kHalfDw], fb[kHalfDw];
+            Unpack<WA, B>::run(pa, j, fa);
+            Unpack<WB, B>::run(pb, j, fb);
+            const v16i d = block_mfma<B>(fa, fb);
+            const int ebj = (int)((eb >> (8 * j)) & 0xFFu) + eadj;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int e = (int)((ea[r] >> (8 * j)) & 0xFFu) + ebj;
+                acc[r] += __builtin_ldexpf((float)d[r], e);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wave][r][lane] = acc[r];
+    __syncthreads();
+    // 256 (r, lane) sums, one per thread of the first four waves
+    for (int t = threadIdx.x; t < 256; t += NW * 64) {
+        const int r = t >> 6, l = t & 63;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += red[w][r][l];
+        const int64_t m = 4 * (l >> 5) + r;
+        const int64_t n = gb * 32 + (l & 31);
+        if (m < g.M && n < g.N) g.Y[bz * g.batch_stride_y + m * g.ldy + n] = s;
+    }
+}
+
+constexpr int kGemvWaves = 8;
+
+template <int WA, int WB, int B>
+mx_status launch(const GemmArgs& g, int64_t batch, hipStream_t st) {
+    if (g.M <= 8) {
+        dim3 grid((unsigned)g.groupsB, (unsigned)batch);
+        hipLaunchKernelGGL((gemv_fragment_kernel<WA, WB, B, kGemvWaves>), grid, dim3(kGemvWaves * 64), 0, st, g);
+    } else {
+        dim3 grid((unsigned)ceil_div(g.groupsB, 4), (unsigned)ceil_div(g.groupsA, 4), (unsigned)batch);
+        hipLaunchKernelGGL((gemm_fragment_kernel<WA, WB, B>), grid, dim3(256), 0, st, g);
+    }
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+#define MX_SW(W_, NAME, ...)                                        \
+    switch (W_) {                                                   \
+        case 2: { constexpr int NAME = 2; __VA_ARGS__; } break;     \
+        case 3: { constexpr int NAME = 3; __VA_ARGS__; } break;     \
+        case 4: { constexpr int NAME = 4; __VA_ARGS__; } break;     \
+        case 5: { constexpr int NAME = 5; __VA_ARGS__; } break;     \
+        case 6: { constexpr int NAME = 6; __VA_ARGS__; } break;     \
+        case 7: { constexpr int NAME = 7; __VA_ARGS__; } break;     \
+        case 8: { constexpr int NAME = 8; __VA_ARGS__; } break;     \
+        default: return MX_ERR_BAD_ARG;                             \
+    }
+
+template <int B>
+mx_status dispatch_widths(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st) {
+    MX_SW(wa, kWA, MX_SW(wb, kWB, return (launch<kWA, kWB, B>(g, batch, st))));
+    return MX_ERR_BAD_ARG;
+}
+
+}  // namespace
+
+#define MX_CAT2(a, b) a##b
+#define MX_CAT(a, b) MX_CAT2(a, b)
+mx_status MX_CAT(gemm_block, MX_GEMM_BLOCK)(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st) {
+    return dispatch_widths<MX_GEMM_BLOCK>(g, wa, wb, batch, st);
+}
+
+}  // namespace mx

@@ -1,0 +1,131 @@
+// Decode-time linear layer: fp32 activations (M <= 8 rows) are quantized to MXInt and written
+// straight into the fragment layout, then the decode kernel of mx_gemm streams the packed weights.
+// The quantizer arithmetic is the one of mx_quantize (Section 4.1 format; Section 3.2 emulation
+// semantics: quantize the input, then the operator).
+#include "mx_common.h"
+
+namespace mx {
+namespace {
+
+struct LinQuantArgs {
+    const float* x;
+    uint8_t* packed;
+    int64_t M, K, row_stride, chunks;
+    int32_t piece, record, bias, emax;
+};
+
+// One thread per (row m < M, block slot b < 4*chunks).  Slots past K hold zero mantissas.
+// Rows M..31 of the (single) row group are left untouched: the decode kernel never reads them.
+template <int W, int B, int RND>
+__global__ __launch_bounds__(256) void quantize_to_fragments_kernel(LinQuantArgs a) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t slots = a.chunks * 4;
+    if (t >= a.M * slots) return;
+    const int64_t m = t / slots, b = t - m * slots;
+    const int64_t c = b >> 2;
+    const int j = (int)(b & 3);
+    const bool inside = b * B < a.K;
+    float v[B];
+    uint32_t am = 0;
+#pragma unroll
+    for (int k = 0; k < B; ++k) {
+        v[k] = inside ? a.x[m * a.row_stride + b * B + k] : 0.f;
+        uint32_t ab = __float_as_uint(v[k]) & 0x7fffffffu;
+        am = ab > am ? ab : am;
+    }
+    const int ef = (int)(am >> 23);
+    int E = ef == 0 ? -127 : ef - 127;
+    E = E < -a.bias ? -a.bias : E;
+    E = E > a.emax ? a.emax : E;
+    const int shift = (W - 2) - E;
+    constexpr float qmax = (float)((1 << (W - 1)) - 1);
+    uint8_t* rec = a.packed + c * a.record;
+    constexpr int kHalfBytes = B * W / 16;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        // (B/2)*W bits of half h, as bytes
+        uint8_t out[kHalfBytes];
+#pragma unroll
+        for (int d = 0; d < kHalfBytes; ++d) out[d] = 0;
+#pragma unroll
+        for (int k = 0; k < B / 2; ++k) {
+            float s = __builtin_ldexpf(v[h * (B / 2) + k], shift);
+            float r = RND == MX_RNE ? __builtin_rintf(s) : __builtin_truncf(s);
+            r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+            const uint32_t code = (uint32_t)(int)r & ((1u << W) - 1u);
+            int pos = k;                                   // element position inside the half block
+            if (W == 4) {                                  // nibble order e0 e4 e1 e5 e2 e6 e3 e7 per 8
+                const int t8 = k & 7;
+                pos = (k & ~7) + (t8 < 4 ? 2 * t8 : 2 * (t8 - 4) + 1);
+            }
+            const int bit = pos * W;
+            out[bit >> 3] |= (uint8_t)(code << (bit & 7));
+            if ((bit & 7) + W > 8) out[(bit >> 3) + 1] |= (uint8_t)(code >> (8 - (bit & 7)));
+        }
+        uint8_t* dst = rec + (int64_t)(32 * h + m) * a.piece + j * kHalfBytes;
+#pragma unroll
+        for (int d = 0; d < kHalfBytes; ++d) dst[d] = out[d];
+    }
+    rec[64 * a.piece + m * 4 + j] = inside ? (uint8_t)(E + a.bias) : (uint8_t)0;
+}
+
+template <int W, int B>
+mx_status launch_lq(const LinQuantArgs& a, int rnd, hipStream_t st) {
+    const int64_t threads = a.M * a.chunks * 4;
+    dim3 grid((unsigned)ceil_div(threads, 256));
+    if (rnd == MX_RNE)
+        hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RNE>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RTZ>), grid, dim3(256), 0, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+#define MX_SW(W_, NAME, ...)                                        \
+    switch (W_) {                                                   \
+        case 2: { constexpr int NAME = 2; __VA_ARGS__; } break;     \
+        case 3: { constexpr int NAME = 3; __VA_ARGS__; } break;     \
+        case 4: { constexpr int NAME = 4; __VA_ARGS__; } break;     \
+        case 5: { constexpr int NAME = 5; __VA_ARGS__; } break;     \
+        case 6: { constexpr int NAME = 6; __VA_ARGS__; } break;     \
+        case 7: { constexpr int NAME = 7; __VA_ARGS__; } break;     \
+        case 8: { constexpr int NAME = 8; __VA_ARGS__; } break;     \
+        default: return MX_ERR_BAD_ARG;                             \
+    }
+
+}  // namespace
+}  // namespace mx
+
+using namespace mx;
+
+extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
+                               void* A_scratch, const void* B_packed, int64_t N, mx_format fb,
+                               int32_t layout, float* Y, int64_t ldy, void* stream) {
+    if (!format_ok_quant(fx) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
+    if (fx.block != fb.block || fx.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
+    if (!format_ok_gemm(fx)) return MX_ERR_UNSUPPORTED;
+    if (layout != MX_LAYOUT_FRAGMENT) return MX_ERR_BAD_ARG;
+    if (M < 0 || N < 0 || K < 0 || K % fx.block != 0 || row_stride < K || ldy < N) return MX_ERR_BAD_ARG;
+    if (M > 8) return MX_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return MX_OK;
+    if (K > 0 && (!x || !A_scratch || !B_packed)) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)x & 3) || ((uintptr_t)A_scratch & 255)) return MX_ERR_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (K > 0) {
+        const FragGeom ga = frag_geom(M, K, fx.block, fx.mant_bits);
+        LinQuantArgs a;
+        a.x = x; a.packed = (uint8_t*)A_scratch;
+        a.M = M; a.K = K; a.row_stride = row_stride; a.chunks = ga.chunks;
+        a.piece = ga.piece; a.record = ga.record;
+        a.bias = (1 << (fx.exp_bits - 1)) - 1;
+        a.emax = ((1 << fx.exp_bits) - 1) - a.bias;
+        mx_status s = MX_ERR_UNSUPPORTED;
+        switch (fx.block) {
+            case 16: MX_SW(fx.mant_bits, kW, s = (launch_lq<kW, 16>(a, fx.rounding, st))); break;
+            case 32: MX_SW(fx.mant_bits, kW, s = (launch_lq<kW, 32>(a, fx.rounding, st))); break;
+            case 64: MX_SW(fx.mant_bits, kW, s = (launch_lq<kW, 64>(a, fx.rounding, st))); break;
+        }
+        if (s != MX_OK) return s;
+    }
+    return mx_gemm(1, M, N, K, A_scratch, fx, B_packed, fb, layout, Y, ldy, M * ldy, stream);
+}

@@ -1,0 +1,355 @@
+// MXInt block quantizer and its inverse for gfx950.
+//
+// Format: Section 4.1 of the paper (a block shares one e-bit exponent; every element keeps a
+// sign and an m-bit mantissa; w = m + 1 stored bits).  The arithmetic per block is
+//   E = floor(log2 max|x|) clamped to the e-bit range, q = round(x * 2^(w-2-E)) clamped to +-qmax.
+// Everything is done on the fp32 bit pattern (exponent field, v_ldexp_f32, v_rndne_f32), so the
+// result does not depend on any transcendental and is bit-exact by construction.
+//
+// The kernels are bound by HBM traffic: 4 bytes read and w/8 + 1/block bytes written per element.
+#include "mx_common.h"
+
+namespace mx {
+namespace {
+
+// Maximum of v over aligned groups of LPB consecutive lanes (LPB in 1, 2, 4, 8), on the DPP path.
+template <int LPB>
+__device__ __forceinline__ uint32_t group_max_u32(uint32_t v) {
+    if constexpr (LPB >= 2) {
+        uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);  // lane ^ 1
+        v = v > o ? v : o;
+    }
+    if constexpr (LPB >= 4) {
+        uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);  // lane ^ 2
+        v = v > o ? v : o;
+    }
+    if constexpr (LPB >= 8) {
+        uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true);  // 7 - lane within 8
+        v = v > o ? v : o;
+    }
+    return v;
+}
+
+// Shared exponent of a block from the bit pattern of its largest magnitude.
+// Returns E (unbiased, clamped); a zero or subnormal maximum gives the lower clamp.
+__device__ __forceinline__ int block_exponent(uint32_t amax_bits, int bias, int emax) {
+    const int ef = (int)(amax_bits >> 23);
+    int E = ef == 0 ? -127 : ef - 127;   // subnormal maxima have floor(log2) <= -127 <= any lower clamp
+    E = E < -bias ? -bias : E;
+    E = E > emax ? emax : E;
+    return E;
+}
+
+template <int W, int RND>
+__device__ __forceinline__ int quantize_one(float x, int shift) {
+    constexpr float qmax = (float)((1 << (W - 1)) - 1);
+    float v = __builtin_ldexpf(x, shift);
+    float r = RND == MX_RNE ? __builtin_rintf(v) : __builtin_truncf(v);
+    r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+    return (int)r;
+}
+
+// Eight mantissas -> 8*W bits, element i at bits [i*W, (i+1)*W).
+template <int W>
+__device__ __forceinline__ uint64_t pack8(const int* q) {
+    uint64_t s = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s |= (uint64_t)((uint32_t)q[i] & ((1u << W) - 1u)) << (i * W);
+    return s;
+}
+
+template <int W>
+__device__ __forceinline__ void store_stream(uint8_t* dst, uint64_t s) {
+    // dst = base + octet*W: alignment is gcd(W, 8)-ish; pick the widest store that is always aligned
+    if constexpr (W == 8) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)s, (uint32_t)(s >> 32));
+    } else if constexpr (W == 4) {
+        *reinterpret_cast<uint32_t*>(dst) = (uint32_t)s;
+    } else if constexpr (W == 2 || W == 6) {
+#pragma unroll
+        for (int i = 0; i < W / 2; ++i) reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)(s >> (16 * i));
+    } else {
+#pragma unroll
+        for (int i = 0; i < W; ++i) dst[i] = (uint8_t)(s >> (8 * i));
+    }
+}
+
+template <int W>
+__device__ __forceinline__ uint64_t load_stream(const uint8_t* src) {
+    if constexpr (W == 8) {
+        uint2 v = *reinterpret_cast<const uint2*>(src);
+        return (uint64_t)v.x | ((uint64_t)v.y << 32);
+    } else if constexpr (W == 4) {
+        return *reinterpret_cast<const uint32_t*>(src);
+    } else if constexpr (W == 2 || W == 6) {
+        uint64_t s = 0;
+#pragma unroll
+        for (int i = 0; i < W / 2; ++i) s |= (uint64_t)reinterpret_cast<const uint16_t*>(src)[i] << (16 * i);
+        return s;
+    } else {
+        uint64_t s = 0;
+#pragma unroll
+        for (int i = 0; i < W; ++i) s |= (uint64_t)src[i] << (8 * i);
+        return s;
+    }
+}
+
+struct QuantArgs {
+    const float* x;
+    uint8_t* mant;
+    uint8_t* exps;
+    int64_t octets;        // batch*rows*cols/8
+    int64_t row_octets;    // cols/8
+    int64_t rows;          // rows per batch entry
+    int64_t row_stride;
+    int64_t batch_stride;
+    int32_t bias;
+    int32_t emax;
+    int32_t dense;         // x is dense and 16-byte aligned: octet o starts at x + 8*o
+};
+
+// Blocks along the contiguous axis.  One lane owns 8 consecutive elements (two 16-byte loads),
+// LPB = B/8 adjacent lanes own one block.
+template <int W, int B, int RND>
+__global__ __launch_bounds__(256) void quantize_axis1_kernel(QuantArgs a) {
+    constexpr int LPB = B / 8;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    // every lane of a wave runs the same number of iterations (the DPP reductions need whole groups)
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t wave_first = first - (threadIdx.x & 63);
+    for (int64_t wo = wave_first, o = first; wo < a.octets; wo += stride, o += stride) {
+        const bool live = o < a.octets;
+        float v[8];
+        if (live) {
+            const float* src;
+            if (a.dense) {
+                src = a.x + o * 8;
+            } else {
+                const int64_t row = o / a.row_octets, c8 = o - row * a.row_octets;
+                const int64_t b = row / a.rows, r = row - b * a.rows;
+                src = a.x + b * a.batch_stride + r * a.row_stride + c8 * 8;
+            }
+            if (a.dense) {
+                const float4 lo = reinterpret_cast<const float4*>(src)[0];
+                const float4 hi = reinterpret_cast<const float4*>(src)[1];
+                v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
+                v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = src[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = 0.f;
+        }
+        uint32_t am = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t ab = __float_as_uint(v[i]) & 0x7fffffffu;
+            am = ab > am ? ab : am;
+        }
+        am = group_max_u32<LPB>(am);
+        const int E = block_exponent(am, a.bias, a.emax);
+        const int shift = (W - 2) - E;
+        int q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(v[i], shift);
+        if (live) {
+            store_stream<W>(a.mant + o * W, pack8<W>(q));
+            if ((threadIdx.x & (LPB - 1)) == 0) a.exps[o / LPB] = (uint8_t)(E + a.bias);
+        }
+    }
+}
+
+struct QuantAxis0Args {
+    const float* x;
+    uint8_t* mant;
+    uint8_t* exps;
+    int64_t batch, rows, cols, row_stride, batch_stride;
+    int32_t bias, emax;
+};
+
+// Blocks down the rows of each column; the output is the canonical form of the transposed
+// matrix.  One lane owns one block (B strided loads, coalesced across the lanes' columns).
+template <int W, int B, int RND>
+__global__ __launch_bounds__(256) void quantize_axis0_kernel(QuantAxis0Args a) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t rb = blockIdx.y;            // block index along the rows
+    const int64_t b = blockIdx.z;
+    if (c >= a.cols) return;
+    const float* src = a.x + b * a.batch_stride + rb * B * a.row_stride + c;
+    float v[B];
+#pragma unroll
+    for (int i = 0; i < B; ++i) v[i] = src[i * a.row_stride];
+    uint32_t am = 0;
+#pragma unroll
+    for (int i = 0; i < B; ++i) {
+        uint32_t ab = __float_as_uint(v[i]) & 0x7fffffffu;
+        am = ab > am ? ab : am;
+    }
+    const int E = block_exponent(am, a.bias, a.emax);
+    const int shift = (W - 2) - E;
+    const int64_t nb = a.rows / B;
+    uint8_t* mrow = a.mant + (b * a.cols + c) * (a.rows * W / 8) + rb * (B * W / 8);
+#pragma unroll
+    for (int o = 0; o < B / 8; ++o) {
+        int q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(v[o * 8 + i], shift);
+        store_stream<W>(mrow + o * W, pack8<W>(q));
+    }
+    a.exps[(b * a.cols + c) * nb + rb] = (uint8_t)(E + a.bias);
+}
+
+struct DequantArgs {
+    const uint8_t* mant;
+    const uint8_t* exps;
+    float* y;
+    int64_t octets;
+    int32_t bias;
+};
+
+template <int W, int B>
+__global__ __launch_bounds__(256) void dequantize_kernel(DequantArgs a) {
+    constexpr int LPB = B / 8;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < a.octets; o += stride) {
+        const uint64_t s = load_stream<W>(a.mant + o * W);
+        const int sh = (int)a.exps[o / LPB] - a.bias - (W - 2);
+        float r[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            int q = (int)((uint32_t)(s >> (i * W)) << (32 - W)) >> (32 - W);
+            r[i] = __builtin_ldexpf((float)q, sh);
+        }
+        float4* dst = reinterpret_cast<float4*>(a.y + o * 8);
+        dst[0] = make_float4(r[0], r[1], r[2], r[3]);
+        dst[1] = make_float4(r[4], r[5], r[6], r[7]);
+    }
+}
+
+inline int grid_for(int64_t items, int threads, int max_blocks) {
+    int64_t g = ceil_div(items, threads);
+    if (g < 1) g = 1;
+    if (g > max_blocks) g = max_blocks;
+    return (int)g;
+}
+
+template <int W, int B>
+mx_status launch_axis1(const QuantArgs& a, int rnd, hipStream_t st) {
+    // enough resident waves to cover HBM latency; each lane then walks the tensor with a grid stride
+    const int grid = grid_for(a.octets, 256, 256 * 16);
+    if (rnd == MX_RNE)
+        hipLaunchKernelGGL((quantize_axis1_kernel<W, B, MX_RNE>), dim3(grid), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((quantize_axis1_kernel<W, B, MX_RTZ>), dim3(grid), dim3(256), 0, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+template <int W, int B>
+mx_status launch_axis0(const QuantAxis0Args& a, int rnd, hipStream_t st) {
+    dim3 grid((unsigned)ceil_div(a.cols, 256), (unsigned)(a.rows / B), (unsigned)a.batch);
+    if (rnd == MX_RNE)
+        hipLaunchKernelGGL((quantize_axis0_kernel<W, B, MX_RNE>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((quantize_axis0_kernel<W, B, MX_RTZ>), grid, dim3(256), 0, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+template <int W, int B>
+mx_status launch_dequant(const DequantArgs& a, hipStream_t st) {
+    const int grid = grid_for(a.octets, 256, 256 * 16);
+    hipLaunchKernelGGL((dequantize_kernel<W, B>), dim3(grid), dim3(256), 0, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+// Expand (w, block) runtime values into template instances.
+#define MX_SWITCH_W(W_, ...)                                                         \
+    switch (W_) {                                                                    \
+        case 2: { constexpr int kW = 2; __VA_ARGS__; } break;                        \
+        case 3: { constexpr int kW = 3; __VA_ARGS__; } break;                        \
+        case 4: { constexpr int kW = 4; __VA_ARGS__; } break;                        \
+        case 5: { constexpr int kW = 5; __VA_ARGS__; } break;                        \
+        case 6: { constexpr int kW = 6; __VA_ARGS__; } break;                        \
+        case 7: { constexpr int kW = 7; __VA_ARGS__; } break;                        \
+        case 8: { constexpr int kW = 8; __VA_ARGS__; } break;                        \
+        default: return MX_ERR_BAD_ARG;                                              \
+    }
+#define MX_SWITCH_B(B_, ...)                                                         \
+    switch (B_) {                                                                    \
+        case 8: { constexpr int kB = 8; __VA_ARGS__; } break;                        \
+        case 16: { constexpr int kB = 16; __VA_ARGS__; } break;                      \
+        case 32: { constexpr int kB = 32; __VA_ARGS__; } break;                      \
+        case 64: { constexpr int kB = 64; __VA_ARGS__; } break;                      \
+        default: return MX_ERR_UNSUPPORTED;                                          \
+    }
+
+}  // namespace
+}  // namespace mx
+
+using namespace mx;
+
+extern "C" size_t mx_mant_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f) {
+    if (!format_ok_quant(f) || batch < 0 || rows < 0 || cols < 0) return 0;
+    return (size_t)(batch * rows * cols) * f.mant_bits / 8;
+}
+
+extern "C" size_t mx_exps_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f) {
+    if (!format_ok_quant(f) || batch < 0 || rows < 0 || cols < 0) return 0;
+    return (size_t)(batch * rows * cols) / f.block;
+}
+
+extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols,
+                                 int64_t row_stride, int64_t batch_stride, int32_t axis, mx_format f,
+                                 uint8_t* mant, uint8_t* exps, void* stream) {
+    if (!format_ok_quant(f)) return MX_ERR_BAD_ARG;
+    if (batch < 0 || rows < 0 || cols < 0 || row_stride < cols) return MX_ERR_BAD_ARG;
+    if (axis != 0 && axis != 1) return MX_ERR_BAD_ARG;
+    if ((axis == 1 ? cols : rows) % f.block != 0) return MX_ERR_BAD_ARG;
+    if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
+    if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
+    if (!x || !mant || !exps) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)x & 3) || ((uintptr_t)mant & 15)) return MX_ERR_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int bias = (1 << (f.exp_bits - 1)) - 1;
+    const int emax = ((1 << f.exp_bits) - 1) - bias;
+    if (axis == 1) {
+        QuantArgs a;
+        a.x = x; a.mant = mant; a.exps = exps;
+        a.octets = batch * rows * (cols / 8);
+        a.row_octets = cols / 8;
+        a.rows = rows; a.row_stride = row_stride; a.batch_stride = batch_stride;
+        a.bias = bias; a.emax = emax;
+        const bool dense_rows = row_stride == cols && (batch == 1 || batch_stride == rows * cols);
+        a.dense = dense_rows && (((uintptr_t)x & 15) == 0);
+        MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_axis1<kW, kB>(a, f.rounding, st))));
+    } else {
+        if (cols > 0x7fffffffLL || rows / f.block > 65535 || batch > 65535) return MX_ERR_UNSUPPORTED;
+        QuantAxis0Args a;
+        a.x = x; a.mant = mant; a.exps = exps;
+        a.batch = batch; a.rows = rows; a.cols = cols;
+        a.row_stride = row_stride; a.batch_stride = batch_stride;
+        a.bias = bias; a.emax = emax;
+        MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_axis0<kW, kB>(a, f.rounding, st))));
+    }
+    return MX_ERR_UNSUPPORTED;
+}
+
+extern "C" mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows,
+                                   int64_t cols, mx_format f, float* y, void* stream) {
+    if (!format_ok_quant(f)) return MX_ERR_BAD_ARG;
+    if (batch < 0 || rows < 0 || cols < 0 || cols % f.block != 0) return MX_ERR_BAD_ARG;
+    if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
+    if (!mant || !exps || !y) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)y & 15) || ((uintptr_t)mant & 15)) return MX_ERR_BAD_ARG;
+    DequantArgs a;
+    a.mant = mant; a.exps = exps; a.y = y;
+    a.octets = batch * rows * (cols / 8);
+    a.bias = (1 << (f.exp_bits - 1)) - 1;
+    hipStream_t st = (hipStream_t)stream;
+    MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_dequant<kW, kB>(a, st))));
+    return MX_ERR_UNSUPPORTED;
+}

@@ -1,0 +1,86 @@
+"""Host-side checks of the C-ABI library: it loads, exports what include/mx.h declares, does the
+size accounting of the format, and rejects bad arguments before any launch.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2307_15517_amd import mx
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(mx.LIB_PATH):
+        from paper_2307_15517_amd import build
+        build.build(verbose=False)
+    return mx.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "mx.h")).read()
+    declared = re.findall(r"MX_API\s+[\w\s\*]+?\b(mx_\w+)\s*\(", header)
+    assert set(declared) == set(mx.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert mx.mx_version() >= 100
+    assert mx.status_string(mx.MX_OK) == "ok" and "bad" in mx.status_string(mx.MX_ERR_BAD_ARG)
+
+
+def test_size_accounting_matches_eq1(lib):
+    # Section 4.1, Eq. 1: p = e/prod(B) + m + 1 bits per element; MXInt((16,2),8,7) -> 8.25
+    f = mx.fmt(32, 8)
+    n = 64 * 4096
+    assert 8 * (mx.mx_mant_bytes(1, 64, 4096, f) + mx.mx_exps_bytes(1, 64, 4096, f)) / n == 8.25
+    # the fragment layout keeps that density when no padding is needed (rows % 32 == 0, cols % (4*block) == 0)
+    for block, w in [(16, 4), (32, 8), (16, 6), (64, 3)]:
+        f = mx.fmt(block, w)
+        assert mx.mx_packed_bytes(1, 64, 1024, f) * 8 / (64 * 1024) == w + 8 / block
+    # 4-bit weights with one exponent byte per 16: 0.5625 bytes per weight
+    assert mx.mx_packed_bytes(1, 5120, 5120, mx.fmt(16, 4)) == 0.5625 * 5120 * 5120
+    assert mx.mx_packed_bytes(3, 33, 100 * 16, mx.fmt(16, 4)) % 256 == 0
+    assert mx.mx_packed_bytes(1, 32, 48, mx.fmt(32, 4)) == 0          # cols not a whole number of blocks
+    assert mx.mx_mant_bytes(1, 4, 64, mx.fmt(12, 4)) == 0             # bad block
+
+
+def test_bad_arguments_are_rejected_before_any_launch(lib):
+    f = mx.fmt(32, 8)
+    q = lambda **kw: mx.mx_quantize(kw.get("x", 256), 1, kw.get("rows", 4), kw.get("cols", 64),
+                                    kw.get("rs", 64), 0, kw.get("axis", 1), kw.get("f", f),
+                                    kw.get("mant", 256), kw.get("exps", 256), stream=0, check=False)
+    assert q(x=0) == mx.MX_ERR_BAD_ARG                                  # null pointer
+    assert q(cols=48, rs=48) == mx.MX_ERR_BAD_ARG                       # not a whole number of blocks
+    assert q(rows=-1) == mx.MX_ERR_BAD_ARG
+    assert q(rs=32) == mx.MX_ERR_BAD_ARG                                # row stride below cols
+    assert q(axis=2) == mx.MX_ERR_BAD_ARG
+    assert q(x=258) == mx.MX_ERR_BAD_ARG                                # misaligned
+    assert q(f=mx.fmt(32, 9)) == mx.MX_ERR_BAD_ARG
+    assert q(f=mx.fmt(32, 1)) == mx.MX_ERR_BAD_ARG
+    assert q(f=mx.fmt(32, 8, exp_bits=9)) == mx.MX_ERR_BAD_ARG
+    assert q(f=mx.fmt(32, 8, rounding=5)) == mx.MX_ERR_BAD_ARG
+    assert q(f=mx.fmt(24, 8), cols=48, rs=48) == mx.MX_ERR_BAD_ARG
+    assert q(rows=0) == mx.MX_OK                                        # empty input: nothing to do
+    assert mx.mx_dequantize(0, 256, 1, 4, 64, f, 256, stream=0, check=False) == mx.MX_ERR_BAD_ARG
+    assert mx.mx_pack(256, 256, 1, 4, 64, mx.fmt(8, 8), 0, 256, stream=0, check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_pack(256, 256, 1, 4, 64, f, 7, 256, stream=0, check=False) == mx.MX_ERR_BAD_ARG
+    assert mx.mx_pack(256, 256, 1, 4, 64, f, 0, 300, stream=0, check=False) == mx.MX_ERR_BAD_ARG  # alignment
+    g = lambda **kw: mx.mx_gemm(1, kw.get("M", 16), kw.get("N", 32), kw.get("K", 64), kw.get("A", 256),
+                                kw.get("fa", f), kw.get("B", 512), kw.get("fb", mx.fmt(32, 4)), 0,
+                                kw.get("Y", 1024), kw.get("ldy", 32), 0, stream=0, check=False)
+    assert g(fb=mx.fmt(16, 4)) == mx.MX_ERR_BAD_ARG                     # block sizes differ
+    assert g(K=48) == mx.MX_ERR_BAD_ARG
+    assert g(ldy=16) == mx.MX_ERR_BAD_ARG
+    assert g(A=0) == mx.MX_ERR_BAD_ARG
+    assert g(Y=0) == mx.MX_ERR_BAD_ARG
+    assert g(fa=mx.fmt(8, 8), fb=mx.fmt(8, 4)) == mx.MX_ERR_UNSUPPORTED
+    assert g(M=0) == mx.MX_OK
+    assert mx.mx_linear(256, 9, 64, 64, f, 256, 512, 32, mx.fmt(32, 4), 0, 1024, 32, stream=0,
+                        check=False) == mx.MX_ERR_UNSUPPORTED            # decode path is M <= 8
+    with pytest.raises(mx.MxError):
+        mx.mx_quantize(0, 1, 4, 64, 64, 0, 1, f, 256, 256, stream=0)
+
+
+def test_struct_layout():
+    assert ctypes.sizeof(mx.mx_format) == 16
