@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the MXInt hot path on one MI355X.
+
+One step = one pass of the whole path over the LLaMA-7B-shaped prefill linears (M = 2048 tokens;
+4096x4096, 4096x11008, 11008x4096; block 32, activations 8 bits, weights 4 bits): for each linear,
+mx_quantize of the fp32 activations, mx_pack, mx_gemm against the pre-packed weights.  All inputs
+are seeded synthetic tensors already resident in HBM.  The step's value is 2*M*N*K summed over the
+three linears divided by the wall time of the step (quantizer and pack included).
+
+Besides the contract fields the JSON line carries
+  roofline      the product kernel: algorithmic 2*M*N*K per launch / average launch duration
+                (HIP events around every mx_gemm of the timed region) against the int8 MFMA peak;
+  kernels       HBM-bound kernels timed on their own over rings of distinct buffers larger than the
+                last-level cache: the quantizer (GB/s) and the decode linear (LLaMA-13B shapes);
+  cpu_baseline  the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+INT8_MFMA_PEAK_TOPS = 5000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernels", action="store_true", help="skip the separate quantizer / decode timings")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path has no multi-GPU part",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2307_15517_amd import inputs, mx
+
+    mx.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L = mx.MX_LAYOUT_FRAGMENT
+
+    # ---------------------------------------------------------------- workload: LLaMA-7B prefill linears
+    cases = inputs.llama7b_prefill()
+    ring = 6                      # distinct activation buffers per linear: 6 * (33.5 + 33.5 + 90) MB > 256 MB cache
+    work = []
+    for case in cases:
+        x, wt = inputs.make(case)
+        fa, fb = mx.fmt(case.block, case.wx), mx.fmt(case.block, case.ww)
+        wd = torch.from_numpy(wt).to(dev)
+        bm, be = mx.quantize(wd, fb)
+        B = mx.pack(bm, be, 1, case.N, case.K, fb)
+        del wd, bm, be
+        xs = [torch.from_numpy(x).to(dev)]
+        for r in range(1, ring):
+            xs.append(torch.roll(xs[0], shifts=r, dims=0).contiguous())
+        w = dict(case=case, fa=fa, fb=fb, B=B, xs=xs,
+                 mant=torch.empty(mx.mx_mant_bytes(1, case.M, case.K, fa), dtype=torch.uint8, device=dev),
+                 exps=torch.empty(mx.mx_exps_bytes(1, case.M, case.K, fa), dtype=torch.uint8, device=dev),
+                 A=torch.empty(mx.mx_packed_bytes(1, case.M, case.K, fa, L), dtype=torch.uint8, device=dev),
+                 Y=[torch.empty((case.M, case.N), dtype=torch.float32, device=dev) for _ in range(2)],
+                 ops=2.0 * case.M * case.N * case.K)
+        work.append(w)
+    total_ops = sum(w["ops"] for w in work)
+    gemm_events = []
+
+    def step(i, timed):
+        for w in work:
+            c = w["case"]
+            x = w["xs"][i % ring]
+            mx.mx_quantize(x, 1, c.M, c.K, c.K, 0, 1, w["fa"], w["mant"], w["exps"])
+            mx.mx_pack(w["mant"], w["exps"], 1, c.M, c.K, w["fa"], L, w["A"])
+            if timed:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            mx.mx_gemm(1, c.M, c.N, c.K, w["A"], w["fa"], w["B"], w["fb"], L, w["Y"][i % 2], c.N, 0)
+            if timed:
+                e1.record()
+                gemm_events.append((e0, e1, w["ops"]))
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = t1 - t0
+    ms_per_step = 1e3 * sec / args.steps
+    value = total_ops * args.steps / sec / 1e12
+
+    gemm_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in gemm_events)
+    gemm_ops = sum(o for _, _, o in gemm_events)
+    achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    roofline = {"kernel": "mx_gemm (int8 MFMA, block-exponent epilogue)", "bound": "mfma",
+                "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                "avg_launch_ms": round(gemm_ms / len(gemm_events), 4)}
+
+    # ---------------------------------------------------------------- HBM-bound kernels on their own
+    kernels = {}
+    if not args.no_kernels:
+        def time_launches(fn, n, reps=3):
+            best = None
+            for _ in range(reps):
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(n):
+                    fn(i)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / n
+                best = ms if best is None else min(best, ms)
+            return best
+
+        # quantizer: 4 bytes read + w/8 + 1/block bytes written per element; ring of 40 buffers = 1.3 GB
+        w0 = work[0]
+        c = w0["case"]
+        qring = [torch.randn((c.M, c.K), dtype=torch.float32, device=dev) for _ in range(40)]
+        ms = time_launches(lambda i: mx.mx_quantize(qring[i % 40], 1, c.M, c.K, c.K, 0, 1, w0["fa"],
+                                                    w0["mant"], w0["exps"]), 80)
+        qbytes = c.M * c.K * (4 + c.wx / 8 + 1 / c.block)
+        kernels["quantize_2048x4096_w8_b32"] = {
+            "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
+        del qring
+        # decode linear, LLaMA-13B shapes: 0.5625*N*K + 4*M*K + 4*M*N bytes per call
+        for M in (1, 4, 8):
+            for dc in inputs.llama13b_decode(M):
+                fa, fb = mx.fmt(dc.block, dc.wx), mx.fmt(dc.block, dc.ww)
+                x, wt = inputs.make(dc)
+                wd = torch.from_numpy(wt).to(dev)
+                bm, be = mx.quantize(wd, fb)
+                B0 = mx.pack(bm, be, 1, dc.N, dc.K, fb)
+                nring = max(2, int(1.3e9 // B0.numel()))
+                Bs = [B0] + [B0.clone() for _ in range(nring - 1)]
+                xd = torch.from_numpy(x).to(dev)
+                scratch = torch.zeros(mx.mx_packed_bytes(1, M, dc.K, fa, L), dtype=torch.uint8, device=dev)
+                y = torch.empty((M, dc.N), dtype=torch.float32, device=dev)
+                ms = time_launches(lambda i: mx.mx_linear(xd, M, dc.K, dc.K, fa, scratch, Bs[i % nring],
+                                                          dc.N, fb, L, y, dc.N), 2 * nring)
+                nbytes = 0.5625 * dc.N * dc.K + 4 * M * dc.K + 4 * M * dc.N
+                kernels["linear_%s_M%d" % (dc.name, M)] = {
+                    "GBps": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                    "us": round(ms * 1e3, 2), "bytes": int(nbytes)}
+                del Bs, B0, wd, bm, be
+
+    # ---------------------------------------------------------------- the oracle on the host cores
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mx_oracle as orc
+        case = cases[0]
+        x, wt = inputs.make(case)
+        threads = orc.set_threads(0)
+        rows = case.M          # the whole first linear: a few seconds on the machine's cores
+        t0 = time.perf_counter()
+        qa, ea = orc.quantize(x[:rows], case.block, case.wx)
+        qb, eb = orc.quantize(wt, case.block, case.ww)
+        orc.gemm(qa, ea, case.wx, qb, eb, case.ww, case.block)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(2.0 * rows * case.N * case.K / dt / 1e12, 5), "unit": "TOP/s", "cores": threads,
+               "kind": "oracle", "seconds": round(dt, 2),
+               "sample": "%s: quantize %d of %d activation rows and all weights, then the product for those rows "
+                         "(2*%d*%d*%d ops), C oracle with OpenMP over rows" % (case.name, rows, case.M, rows,
+                                                                              case.N, case.K)}
+
+    out = {
+        "metric": "MXInt GEMM TOPS + quantize/GEMV GB/s (% roofline) at LLaMA-7B linear shapes",
+        "value": round(value, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "llama7b_prefill_M2048: quantize+pack+gemm over 4096x4096, 4096x11008, "
+                               "11008x4096; block 32, act 8 bits, weight 4 bits"},
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

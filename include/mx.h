@@ -69,9 +69,16 @@ typedef enum { MX_OK = 0, MX_ERR_BAD_ARG = 1, MX_ERR_UNSUPPORTED = 2, MX_ERR_DEV
  *   MX_LAYOUT_FRAGMENT: w bits per element + 1 byte per block, i.e. exactly the
  *       density of the canonical form (Eq. 1), arranged in the order the matrix
  *       cores' lanes consume it.  Rows are padded to a multiple of 32 and columns to
- *       a multiple of 4 blocks with zeros.  Either operand of mx_gemm, any M.
+ *       a multiple of 4 blocks with zeros.  Either operand of mx_gemm, any M, block 16, 32 or 64.
+ *   MX_LAYOUT_MATRIX: the operand as the block-scaled matrix cores of gfx950 read it (block 32 or
+ *       64 only): every mantissa is carried exactly in 6-bit float codes, one code for up to 4
+ *       stored bits and two codes (q = 16*h + l) for 5..8 bits, i.e. 6 or 12 bits per element plus the
+ *       exponent bytes; rows are padded to 32 (64 for one-code operands) and K to 256.  This is the
+ *       layout of the compute-bound (prefill) path.  Restriction: exponent bytes above 250
+ *       (|x| >= 2^124 at e = 8) are not representable next to the +4 offset of the high code; such
+ *       blocks give unspecified products.  Both operands of one mx_gemm use the same layout.
  */
-enum { MX_LAYOUT_FRAGMENT = 0 };
+enum { MX_LAYOUT_FRAGMENT = 0, MX_LAYOUT_MATRIX = 1 };
 
 /* Library version: major*10000 + minor*100 + patch. */
 MX_API int32_t mx_version(void);
@@ -124,6 +131,16 @@ MX_API size_t mx_packed_bytes(int64_t batch, int64_t rows, int64_t cols, mx_form
  */
 MX_API mx_status mx_pack(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
                   mx_format f, int32_t layout, void* packed, void* stream);
+
+/*
+ * mx_quantize (axis 1) and mx_pack in one pass over the fp32 input: `packed` receives exactly
+ * the bytes that mx_pack would produce from mx_quantize's output, without the canonical form
+ * going through memory.  Same argument rules as mx_quantize; for MX_LAYOUT_MATRIX x must be
+ * 16-byte aligned and the strides multiples of 4 elements (else MX_ERR_UNSUPPORTED).
+ */
+MX_API mx_status mx_quantize_pack(const float* x, int64_t batch, int64_t rows, int64_t cols,
+                                  int64_t row_stride, int64_t batch_stride, mx_format f, int32_t layout,
+                                  void* packed, void* stream);
 
 /* Exact inverse of mx_pack. */
 MX_API mx_status mx_unpack(const void* packed, int64_t batch, int64_t rows, int64_t cols, mx_format f,

@@ -1,6 +1,12 @@
 // Host entry point of the MXInt x MXInt product: argument checks and dispatch on the block size.
 #include "mx_gemm.h"
 
+namespace mx {
+bool matrix_format_ok(const mx_format& f);
+mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, mx_format fa, const void* B,
+                      mx_format fb, float* Y, int64_t ldy, int64_t batch_stride_y, hipStream_t st);
+}  // namespace mx
+
 using namespace mx;
 
 extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed,
@@ -8,8 +14,8 @@ extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, con
                              int64_t ldy, int64_t batch_stride_y, void* stream) {
     if (!format_ok_quant(fa) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
     if (fa.block != fb.block || fa.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
-    if (!format_ok_gemm(fa)) return MX_ERR_UNSUPPORTED;
-    if (layout != MX_LAYOUT_FRAGMENT) return MX_ERR_BAD_ARG;
+    if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
+    if (layout == MX_LAYOUT_FRAGMENT ? !format_ok_gemm(fa) : !matrix_format_ok(fa)) return MX_ERR_UNSUPPORTED;
     if (batch < 0 || M < 0 || N < 0 || K < 0 || K % fa.block != 0 || ldy < N) return MX_ERR_BAD_ARG;
     if (batch > 1 && batch_stride_y < (M - 1) * ldy + N) return MX_ERR_BAD_ARG;
     if (batch == 0 || M == 0 || N == 0) return MX_OK;
@@ -17,6 +23,8 @@ extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, con
     if (K > 0 && (!A_packed || !B_packed)) return MX_ERR_BAD_ARG;
     if (((uintptr_t)A_packed & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
     if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    if (layout == MX_LAYOUT_MATRIX)
+        return gemm_scaled(batch, M, N, K, A_packed, fa, B_packed, fb, Y, ldy, batch_stride_y, (hipStream_t)stream);
     const FragGeom ga = frag_geom(M, K, fa.block, fa.mant_bits);
     const FragGeom gb = frag_geom(N, K, fb.block, fb.mant_bits);
     if (ceil_div(ga.groups, 4) > 65535) return MX_ERR_UNSUPPORTED;

@@ -6,8 +6,19 @@
 // every dword are stored in the order e0 e4 e1 e5 e2 e6 e3 e7, so that (d << 4) & 0xF0F0F0F0 and
 // d & 0xF0F0F0F0 are the two int8x4 words (times 16) in element order.
 #include "mx_common.h"
+#include "mx_matrix.h"
 
 namespace mx {
+
+// defined in mx_pack_matrix.hip / mx_linear.hip
+bool matrix_format_ok(const mx_format& f);
+mx_status pack_matrix(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
+                      mx_format f, uint8_t* packed, bool pack, hipStream_t st);
+mx_status quantize_pack_matrix(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                               int64_t batch_stride, mx_format f, uint8_t* packed, hipStream_t st);
+mx_status quantize_pack_fragment(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                                 int64_t batch_stride, mx_format f, uint8_t* packed, hipStream_t st);
+
 namespace {
 
 __device__ __forceinline__ uint32_t nibble_interleave(uint32_t d) {
@@ -89,8 +100,9 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a) {
 }
 
 mx_status check_pack_args(int64_t batch, int64_t rows, int64_t cols, const mx_format& f, int32_t layout) {
-    if (!format_ok_gemm(f)) return format_ok_quant(f) ? MX_ERR_UNSUPPORTED : MX_ERR_BAD_ARG;
-    if (layout != MX_LAYOUT_FRAGMENT) return MX_ERR_BAD_ARG;
+    if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
+    if (!format_ok_quant(f)) return MX_ERR_BAD_ARG;
+    if (layout == MX_LAYOUT_FRAGMENT ? !format_ok_gemm(f) : !matrix_format_ok(f)) return MX_ERR_UNSUPPORTED;
     if (batch < 0 || rows < 0 || cols < 0 || cols % f.block != 0) return MX_ERR_BAD_ARG;
     return MX_OK;
 }
@@ -104,6 +116,7 @@ mx_status run_pack(const uint8_t* mant, const uint8_t* exps, int64_t batch, int6
     if (!mant || !exps || !packed) return MX_ERR_BAD_ARG;
     if (((uintptr_t)packed & 255) || ((uintptr_t)mant & 15)) return MX_ERR_BAD_ARG;
     if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    if (layout == MX_LAYOUT_MATRIX) return pack_matrix(mant, exps, batch, rows, cols, f, packed, PACK, (hipStream_t)stream);
     FragGeom g = frag_geom(rows, cols, f.block, f.mant_bits);
     PackArgs a;
     a.mant = mant; a.exps = exps; a.packed = packed;
@@ -123,6 +136,7 @@ using namespace mx;
 
 extern "C" size_t mx_packed_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f, int32_t layout) {
     if (check_pack_args(batch, rows, cols, f, layout) != MX_OK) return 0;
+    if (layout == MX_LAYOUT_MATRIX) return (size_t)(batch * mat_geom(rows, cols, f.mant_bits).matrix);
     return (size_t)(batch * frag_geom(rows, cols, f.block, f.mant_bits).matrix);
 }
 
@@ -135,4 +149,21 @@ extern "C" mx_status mx_unpack(const void* packed, int64_t batch, int64_t rows, 
                                int32_t layout, uint8_t* mant, uint8_t* exps, void* stream) {
     return run_pack<false>(mant, exps, batch, rows, cols, f, layout,
                            const_cast<uint8_t*>((const uint8_t*)packed), stream);
+}
+
+extern "C" mx_status mx_quantize_pack(const float* x, int64_t batch, int64_t rows, int64_t cols,
+                                      int64_t row_stride, int64_t batch_stride, mx_format f, int32_t layout,
+                                      void* packed, void* stream) {
+    mx_status s = check_pack_args(batch, rows, cols, f, layout);
+    if (s != MX_OK) return s;
+    if (row_stride < cols) return MX_ERR_BAD_ARG;
+    if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
+    if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
+    if (!x || !packed || ((uintptr_t)x & 3) || ((uintptr_t)packed & 255)) return MX_ERR_BAD_ARG;
+    if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    if (layout == MX_LAYOUT_MATRIX)
+        return quantize_pack_matrix(x, batch, rows, cols, row_stride, batch_stride, f, (uint8_t*)packed,
+                                    (hipStream_t)stream);
+    return quantize_pack_fragment(x, batch, rows, cols, row_stride, batch_stride, f, (uint8_t*)packed,
+                                  (hipStream_t)stream);
 }

@@ -18,9 +18,11 @@ LIB_PATH = os.path.join(_HERE, "libmx.so")
 MX_RNE, MX_RTZ = 0, 1
 MX_OK, MX_ERR_BAD_ARG, MX_ERR_UNSUPPORTED, MX_ERR_DEVICE = 0, 1, 2, 3
 MX_LAYOUT_FRAGMENT = 0
+MX_LAYOUT_MATRIX = 1
 
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
-           "mx_dequantize", "mx_packed_bytes", "mx_pack", "mx_unpack", "mx_gemm", "mx_linear")
+           "mx_dequantize", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
+           "mx_linear")
 
 
 class mx_format(ctypes.Structure):
@@ -64,10 +66,12 @@ def load() -> ctypes.CDLL:
     lib.mx_dequantize.argtypes = [vp, vp, i64, i64, i64, mx_format, vp, vp]
     lib.mx_packed_bytes.argtypes, lib.mx_packed_bytes.restype = [i64, i64, i64, mx_format, i32], sz
     lib.mx_pack.argtypes = [vp, vp, i64, i64, i64, mx_format, i32, vp, vp]
+    lib.mx_quantize_pack.argtypes = [vp, i64, i64, i64, i64, i64, mx_format, i32, vp, vp]
     lib.mx_unpack.argtypes = [vp, i64, i64, i64, mx_format, i32, vp, vp, vp]
     lib.mx_gemm.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, i64, i64, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
-    for name in ("mx_quantize", "mx_dequantize", "mx_pack", "mx_unpack", "mx_gemm", "mx_linear"):
+    for name in ("mx_quantize", "mx_dequantize", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
+                 "mx_linear"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -138,6 +142,15 @@ def mx_pack(mant, exps, batch, rows, cols, f, layout, packed, stream=None, check
     return s
 
 
+def mx_quantize_pack(x, batch, rows, cols, row_stride, batch_stride, f, layout, packed, stream=None,
+                     check: bool = True) -> int:
+    s = load().mx_quantize_pack(_p(x), batch, rows, cols, row_stride, batch_stride, f, layout, _p(packed),
+                                _stream(stream))
+    if check:
+        _raise(s, "mx_quantize_pack")
+    return s
+
+
 def mx_unpack(packed, batch, rows, cols, f, layout, mant, exps, stream=None, check: bool = True) -> int:
     s = load().mx_unpack(_p(packed), batch, rows, cols, f, layout, _p(mant), _p(exps), _stream(stream))
     if check:
@@ -191,6 +204,19 @@ def pack(mant: torch.Tensor, exps: torch.Tensor, batch: int, rows: int, cols: in
     packed = torch.empty(max(1, mx_packed_bytes(batch, rows, cols, f, layout)), dtype=torch.uint8,
                          device=mant.device)
     mx_pack(mant, exps, batch, rows, cols, f, layout, packed)
+    return packed
+
+
+def quantize_pack(x: torch.Tensor, f: mx_format, layout: int = MX_LAYOUT_FRAGMENT) -> torch.Tensor:
+    """fp32 [rows, cols] or [batch, rows, cols] -> packed operand in one pass."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.stride(-1) == 1
+    if x.dim() == 2:
+        batch, (rows, cols), bs = 1, x.shape, 0
+    else:
+        batch, rows, cols = x.shape
+        bs = x.stride(0)
+    packed = torch.empty(max(1, mx_packed_bytes(batch, rows, cols, f, layout)), dtype=torch.uint8, device=x.device)
+    mx_quantize_pack(x, batch, rows, cols, x.stride(-2), bs, f, layout, packed)
     return packed
 
 
