@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the separate quantizer / decode timings")
+    ap.add_argument("--layout", choices=["matrix", "fragment"], default="matrix",
+                    help="operand layout of the prefill product: block-scaled matrix cores (default) or int8 MFMA")
+    ap.add_argument("--unfused", action="store_true", help="mx_quantize + mx_pack instead of mx_quantize_pack")
     return ap.parse_args()
 
 
@@ -54,7 +57,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    L = mx.MX_LAYOUT_FRAGMENT
+    L = mx.MX_LAYOUT_MATRIX if args.layout == "matrix" else mx.MX_LAYOUT_FRAGMENT
+    LF = mx.MX_LAYOUT_FRAGMENT
 
     # ---------------------------------------------------------------- workload: LLaMA-7B prefill linears
     cases = inputs.llama7b_prefill()
@@ -65,7 +69,7 @@ def main():
         fa, fb = mx.fmt(case.block, case.wx), mx.fmt(case.block, case.ww)
         wd = torch.from_numpy(wt).to(dev)
         bm, be = mx.quantize(wd, fb)
-        B = mx.pack(bm, be, 1, case.N, case.K, fb)
+        B = mx.pack(bm, be, 1, case.N, case.K, fb, L)
         del wd, bm, be
         xs = [torch.from_numpy(x).to(dev)]
         for r in range(1, ring):
@@ -84,8 +88,11 @@ def main():
         for w in work:
             c = w["case"]
             x = w["xs"][i % ring]
-            mx.mx_quantize(x, 1, c.M, c.K, c.K, 0, 1, w["fa"], w["mant"], w["exps"])
-            mx.mx_pack(w["mant"], w["exps"], 1, c.M, c.K, w["fa"], L, w["A"])
+            if args.unfused:
+                mx.mx_quantize(x, 1, c.M, c.K, c.K, 0, 1, w["fa"], w["mant"], w["exps"])
+                mx.mx_pack(w["mant"], w["exps"], 1, c.M, c.K, w["fa"], L, w["A"])
+            else:
+                mx.mx_quantize_pack(x, 1, c.M, c.K, c.K, 0, w["fa"], L, w["A"])
             if timed:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
@@ -110,7 +117,9 @@ def main():
     gemm_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in gemm_events)
     gemm_ops = sum(o for _, _, o in gemm_events)
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
-    roofline = {"kernel": "mx_gemm (int8 MFMA, block-exponent epilogue)", "bound": "mfma",
+    kname = ("mx_gemm (block-scaled fp6 MFMA, two mantissa pieces for 8-bit activations)" if args.layout == "matrix"
+             else "mx_gemm (int8 MFMA, block-exponent epilogue)")
+    roofline = {"kernel": kname, "bound": "mfma",
                 "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
                 "avg_launch_ms": round(gemm_ms / len(gemm_events), 4)}
@@ -142,6 +151,13 @@ def main():
         kernels["quantize_2048x4096_w8_b32"] = {
             "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
             "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
+        if args.layout == "matrix":
+            ms = time_launches(lambda i: mx.mx_quantize_pack(qring[i % 40], 1, c.M, c.K, c.K, 0, w0["fa"], L,
+                                                             w0["A"]), 80)
+            pbytes = c.M * c.K * 4 + mx.mx_packed_bytes(1, c.M, c.K, w0["fa"], L)
+            kernels["quantize_pack_matrix_2048x4096_w8_b32"] = {
+                "GBps": round(pbytes / ms / 1e6, 1), "frac_hbm": round(pbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                "us": round(ms * 1e3, 2), "bytes": int(pbytes)}
         del qring
         # decode linear, LLaMA-13B shapes: 0.5625*N*K + 4*M*K + 4*M*N bytes per call
         for M in (1, 4, 8):
@@ -150,14 +166,14 @@ def main():
                 x, wt = inputs.make(dc)
                 wd = torch.from_numpy(wt).to(dev)
                 bm, be = mx.quantize(wd, fb)
-                B0 = mx.pack(bm, be, 1, dc.N, dc.K, fb)
+                B0 = mx.pack(bm, be, 1, dc.N, dc.K, fb, LF)
                 nring = max(2, int(1.3e9 // B0.numel()))
                 Bs = [B0] + [B0.clone() for _ in range(nring - 1)]
                 xd = torch.from_numpy(x).to(dev)
-                scratch = torch.zeros(mx.mx_packed_bytes(1, M, dc.K, fa, L), dtype=torch.uint8, device=dev)
+                scratch = torch.zeros(mx.mx_packed_bytes(1, M, dc.K, fa, LF), dtype=torch.uint8, device=dev)
                 y = torch.empty((M, dc.N), dtype=torch.float32, device=dev)
                 ms = time_launches(lambda i: mx.mx_linear(xd, M, dc.K, dc.K, fa, scratch, Bs[i % nring],
-                                                          dc.N, fb, L, y, dc.N), 2 * nring)
+                                                          dc.N, fb, LF, y, dc.N), 2 * nring)
                 nbytes = 0.5625 * dc.N * dc.K + 4 * M * dc.K + 4 * M * dc.N
                 kernels["linear_%s_M%d" % (dc.name, M)] = {
                     "GBps": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
@@ -187,7 +203,8 @@ def main():
         "metric": "MXInt GEMM TOPS + quantize/GEMV GB/s (% roofline) at LLaMA-7B linear shapes",
         "value": round(value, 2), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "vs_baseline": None, "dtype": "fp6(exact int pieces)+fp32 acc" if args.layout == "matrix" else "int8",
+        "data": "synthetic",
         "config": {"workload": "llama7b_prefill_M2048: quantize+pack+gemm over 4096x4096, 4096x11008, "
                                "11008x4096; block 32, act 8 bits, weight 4 bits"},
         "roofline": roofline, "kernels": kernels, "cpu_baseline": cpu,

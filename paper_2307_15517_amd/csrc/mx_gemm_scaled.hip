@@ -36,13 +36,13 @@ struct ScaledArgs {
     int64_t matrixA, matrixB;
     int64_t ldy, batch_stride_y;
     int32_t eadj;
-    int32_t tiles_n;               // workgroup tiles along N
+    int32_t tiles_m, tiles_n;      // workgroup tiles along M and N
 };
 
-// 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_addr + 16*L.
-// Written as inline assembly so that the compiler does not serialize every later LDS read behind
-// the copy (it cannot tell the two stages apart); completion is awaited explicitly with
-// s_waitcnt vmcnt(0) before the barrier that publishes a stage.
+// `bytes` (16 or 4) per lane from global memory straight into LDS: lane L's bytes land at
+// lds_addr + bytes*L.  Written as inline assembly so that the compiler does not serialize every
+// later LDS read behind the copy (it cannot tell the stages apart); completion is awaited
+// explicitly with s_waitcnt vmcnt(n) before the barrier that publishes a stage.
 __device__ __forceinline__ void copy16_to_lds(const uint8_t* uniform_src, uint32_t lane_offset,
                                               uint32_t lds_addr) {
     asm volatile(
@@ -53,65 +53,100 @@ __device__ __forceinline__ void copy16_to_lds(const uint8_t* uniform_src, uint32
         : "v"(lane_offset), "s"(uniform_src), "s"(lds_addr)
         : "memory", "m0");
 }
+__device__ __forceinline__ void copy4_to_lds(const uint8_t* uniform_src, uint32_t lane_offset,
+                                             uint32_t lds_addr) {
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dword %0, %1\n\t"
+        :
+        : "v"(lane_offset), "s"(uniform_src), "s"(lds_addr)
+        : "memory", "m0");
+}
 
-template <int PA, int PB, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_scaled_kernel(ScaledArgs g) {
+// s_waitcnt vmcnt(n), every other counter left alone (gfx9 encoding: vmcnt = bits 3:0 and 15:14)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// S: LDS stages.  The stage of step ks is free once its fragments are in registers, i.e. from
+// the barrier of step ks on, so the copy of step ks+S is issued during step ks.
+// OCC: workgroups the register and LDS budget must leave room for on one compute unit.
+template <int PA, int PB, int TM, int TN, int S, int OCC>
+__global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
+    constexpr int kStages = S;
     constexpr int UA = (PA == 2) ? 2 * TM : TM;        // units of the A tile per K step
     constexpr int UB = (PB == 2) ? 2 * TN : TN;
     constexpr int NU = UA + UB;
     constexpr int STAGE = NU * kUnitBytes;
-    constexpr int NLOAD = (3 * NU + 3) / 4;            // 1 KiB wave loads per wave per K step
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr int NLOAD = (3 * NU + 3) / 4;            // 1 KiB wave copies per wave per K step
+    constexpr int RA = TM, RB = TN;                    // row tiles per wave: the wave tile is (32*RA) x (32*RB)
+    constexpr int NT = 2 * TM + 2 * TN;                // row tiles of the workgroup tile (A then B)
+    constexpr int NSC = (NT + 3) / 4;                  // 256-byte scale copies per wave per group of 4 steps
+    constexpr int SCALES = NT * 256;                   // bytes of one scale slot
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];   // kStages stages, then 2 scale slots
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t bn = blockIdx.x % g.tiles_n, bm = blockIdx.x / g.tiles_n;
+    // Workgroup i runs on XCD i % 8, each with its own L2.  Give every XCD one contiguous range of
+    // tiles, numbered with the M tile fastest, so that the tiles resident on an XCD at one time share
+    // their operand rows (all M tiles of a few N tiles) and hit in that L2.
+    const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n, per_xcd = (tiles + 7) / 8;
+    const int64_t tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (tile >= tiles) return;
+    const int64_t bm = tile % g.tiles_m, bn = tile / g.tiles_m;
     const int64_t bz = blockIdx.y;
     const uint8_t* Abase = g.A + bz * g.matrixA;
     const uint8_t* Bbase = g.B + bz * g.matrixB;
+    const int64_t groups = g.ksteps / 4;
 
-    // this wave's share of the global -> LDS copy: load t moves plane (t % 3) of stage unit (t / 3)
+    // this wave's share of the global -> LDS copy: copy t moves 1 KiB number (t % 3) of stage unit (t / 3)
     const uint8_t* src[NLOAD];
     int dst[NLOAD];
 #pragma unroll
     for (int q = 0; q < NLOAD; ++q) {
         int t = q * 4 + wave;
-        if (t >= 3 * NU) t = 3 * NU - 1;               // duplicate the last load instead of branching
-        const int n = t / 3, plane = t - 3 * n;
+        if (t >= 3 * NU) t = 3 * NU - 1;               // duplicate the last copy instead of branching
+        const int n = t / 3, part = t - 3 * n;
         int64_t u;
         const uint8_t* base;
         if (n < UA) {
             u = bm * UA + n;
-            u = u < g.unitsA ? u : g.unitsA - 1;
+            u = u < g.unitsA ? u : g.unitsA - 1;       // tiles past the matrix re-read its last unit (never stored)
             base = Abase;
         } else {
             u = bn * UB + (n - UA);
             u = u < g.unitsB ? u : g.unitsB - 1;
             base = Bbase;
         }
-        src[q] = base + u * g.ksteps * kUnitBytes + plane * 1024;
-        dst[q] = n * kUnitBytes + plane * 1024;
+        src[q] = base + u * g.ksteps * kUnitBytes + part * 1024;
+        dst[q] = n * kUnitBytes + part * 1024;
     }
-    const uint32_t lane16 = lane * 16;
+    // ... and of the scale copies: row tile t of the workgroup tile, 256 bytes per group of four K steps
+    const uint8_t* ssrc[NSC];
+    int sdst[NSC];
+#pragma unroll
+    for (int q = 0; q < NSC; ++q) {
+        int t = q * 4 + wave;
+        if (t >= NT) t = NT - 1;
+        int64_t rt;
+        const uint8_t* base;
+        if (t < 2 * TM) {
+            rt = bm * 2 * TM + t;
+            rt = rt < g.tilesA ? rt : g.tilesA - 1;
+            base = Abase + g.fragA;
+        } else {
+            rt = bn * 2 * TN + (t - 2 * TM);
+            rt = rt < g.tilesB ? rt : g.tilesB - 1;
+            base = Bbase + g.fragB;
+        }
+        ssrc[q] = base + rt * groups * 256;
+        sdst[q] = kStages * STAGE + t * 256;
+    }
+    const uint32_t lane16 = lane * 16, lane4 = lane * 4;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
-
-    // scale dwords: one per row tile per four K steps, read straight from global
-    constexpr int RA = TM, RB = TN;      // row tiles per wave: the wave tile is (32*RA) x (32*RB)
-    const uint32_t* sA[RA];
-    const uint32_t* sB[RB];
-    const int64_t rtA0 = (bm * 2 + wm) * RA, rtB0 = (bn * 2 + wn) * RB;
-#pragma unroll
-    for (int t = 0; t < RA; ++t) {
-        int64_t rt = rtA0 + t;
-        rt = rt < g.tilesA ? rt : g.tilesA - 1;
-        sA[t] = reinterpret_cast<const uint32_t*>(Abase + g.fragA) + rt * (g.ksteps / 4) * 64 + lane;
-    }
-#pragma unroll
-    for (int t = 0; t < RB; ++t) {
-        int64_t rt = rtB0 + t;
-        rt = rt < g.tilesB ? rt : g.tilesB - 1;
-        sB[t] = reinterpret_cast<const uint32_t*>(Bbase + g.fragB) + rt * (g.ksteps / 4) * 64 + lane;
-    }
 
     v16f acc[RA][RB];
 #pragma unroll
@@ -121,14 +156,23 @@ __global__ __launch_bounds__(256) void gemm_scaled_kernel(ScaledArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[ta][tb][r] = 0.f;
 
+    // Copies are always issued in full, with the K step / group clamped to the last one, so that
+    // the number of copies in flight is the same at every step and the vmcnt waits stay exact.
+    auto issue_one = [&](int q, int64_t ks, int stage) {
+        ks = ks < g.ksteps ? ks : g.ksteps - 1;
+        copy16_to_lds(src[q] + ks * kUnitBytes, lane16, lds0 + stage * STAGE + dst[q]);
+    };
     auto issue = [&](int64_t ks, int stage) {
 #pragma unroll
-        for (int q = 0; q < NLOAD; ++q)
-            copy16_to_lds(src[q] + ks * kUnitBytes, lane16, lds0 + stage * STAGE + dst[q]);
+        for (int q = 0; q < NLOAD; ++q) issue_one(q, ks, stage);
+    };
+    auto issue_scale_one = [&](int q, int64_t grp, int slot) {
+        grp = grp < groups ? grp : groups - 1;
+        copy4_to_lds(ssrc[q] + grp * 256, lane4, lds0 + slot * SCALES + sdst[q]);
     };
 
     // fragment registers, two sets: the MFMAs of a K step run from one set while the LDS reads of
-    // the next step fill the other.  [set][tile][piece] -> 8 dwords (6 used)
+    // the next step fill the other.
     struct Frag { int d[6]; };
     Frag fa[2][RA][PA], fb[2][RB][PB];
     auto load_unit = [&](const uint8_t* u, Frag& f0, Frag& f1) {     // u: unit base in LDS
@@ -144,105 +188,104 @@ __global__ __launch_bounds__(256) void gemm_scaled_kernel(ScaledArgs g) {
     auto operand = [](const Frag& f) {       // the fp6 forms read six of the eight operand dwords
         return v8i{f.d[0], f.d[1], f.d[2], f.d[3], f.d[4], f.d[5], 0, 0};
     };
-    auto read_frags = [&](int stage, auto setc) {
+    // the units this wave reads per K step: first those of A, then those of B
+    constexpr int NUA = (PA == 2) ? RA : RA / 2, NUB = (PB == 2) ? RB : RB / 2;
+    auto read_unit = [&](int n, int stage, auto setc) {
         constexpr int set = decltype(setc)::value;
         const uint8_t* st = smem + stage * STAGE;
-        if constexpr (PA == 2) {
-#pragma unroll
-            for (int t = 0; t < RA; ++t) load_unit(st + (wm * RA + t) * kUnitBytes, fa[set][t][0], fa[set][t][1]);
+        if (n < NUA) {
+            if constexpr (PA == 2) load_unit(st + (wm * RA + n) * kUnitBytes, fa[set][n][0], fa[set][n][1]);
+            else load_unit(st + (wm * NUA + n) * kUnitBytes, fa[set][2 * n][0], fa[set][2 * n + 1][0]);
         } else {
-#pragma unroll
-            for (int t = 0; t < RA; t += 2)
-                load_unit(st + ((wm * RA + t) / 2) * kUnitBytes, fa[set][t][0], fa[set][t + 1][0]);
-        }
-        if constexpr (PB == 2) {
-#pragma unroll
-            for (int t = 0; t < RB; ++t)
-                load_unit(st + (UA + wn * RB + t) * kUnitBytes, fb[set][t][0], fb[set][t][1]);
-        } else {
-#pragma unroll
-            for (int t = 0; t < RB; t += 2)
-                load_unit(st + (UA + (wn * RB + t) / 2) * kUnitBytes, fb[set][t][0], fb[set][t + 1][0]);
+            const int t = n - NUA;
+            if constexpr (PB == 2) load_unit(st + (UA + wn * RB + t) * kUnitBytes, fb[set][t][0], fb[set][t][1]);
+            else load_unit(st + (UA + wn * NUB + t) * kUnitBytes, fb[set][2 * t][0], fb[set][2 * t + 1][0]);
         }
     };
 
-    // Pipeline: at the top of step ks the copy of step ks+1 (issued one step earlier) is awaited
-    // and published with one barrier; that barrier also means every wave has finished reading the
-    // stage of step ks into registers, so the copy of step ks+2 may overwrite it.
-    uint32_t nxA[RA], nxB[RB];           // scale dwords of the next group of four K steps
+    // scale dwords of the current group of four K steps, and the next group's (read during step 3)
+    uint32_t scA[RA], scB[RB], nxA[RA], nxB[RB];
+    auto read_scales = [&](int slot, uint32_t* a, uint32_t* b) {
+        const uint32_t* sc = reinterpret_cast<const uint32_t*>(smem + kStages * STAGE + slot * SCALES) + lane;
 #pragma unroll
-    for (int t = 0; t < RA; ++t) nxA[t] = g.ksteps > 0 ? sA[t][0] : 0u;
+        for (int t = 0; t < RA; ++t) a[t] = sc[(wm * RA + t) * 64];
 #pragma unroll
-    for (int t = 0; t < RB; ++t) nxB[t] = g.ksteps > 0 ? sB[t][0] : 0u;
+        for (int t = 0; t < RB; ++t) b[t] = sc[(2 * TM + wn * RB + t) * 64];
+    };
+
+    // Pipeline.  Queue of copies, oldest first, when step ks starts:  D(ks+1) ... D(ks+S-1), with
+    // the scale copies of a group right behind the data copies of its step 0.  Waiting until only
+    // the newest S-2 steps' copies are outstanding means D(ks+1) has landed; the barrier then
+    // publishes it and tells that every wave is done reading the stage of step ks (read into
+    // registers during step ks-1), which the copy of step ks+S overwrites.
+    // Inside a step the MFMAs (operands already in registers) are issued at once, and the LDS reads
+    // for the next step, the copies for step ks+3 and the scale traffic are slotted between them so
+    // that the matrix pipe never waits for them.
     if (g.ksteps > 0) {
         issue(0, 0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+#pragma unroll
+        for (int q = 0; q < NSC; ++q) issue_scale_one(q, 0, 0);
+#pragma unroll
+        for (int st = 1; st < S; ++st) issue(st, st);
+        wait_vmcnt<(S - 1) * NLOAD>();
         __syncthreads();
-        issue(1, 1);                      // ksteps is a multiple of 4
-        read_frags(0, std::integral_constant<int, 0>{});
+#pragma unroll
+        for (int n = 0; n < NUA + NUB; ++n) read_unit(n, 0, std::integral_constant<int, 0>{});
+        read_scales(0, nxA, nxB);
     }
-    for (int64_t ks4 = 0; ks4 < g.ksteps / 4; ++ks4) {
-        const bool last_group = ks4 + 1 == g.ksteps / 4;
-        uint32_t scA[RA], scAh[RA], scB[RB], scBh[RB];
+    constexpr int NM = PA * PB * RA * RB;              // MFMAs per K step
+    int cur = 0;                                       // stage of the current step: ks % S
+    for (int64_t ks4 = 0; ks4 < groups; ++ks4) {
 #pragma unroll
-        for (int t = 0; t < RA; ++t) {
-            scA[t] = nxA[t];
-            scAh[t] = scA[t] + 0x04040404u;
-        }
+        for (int t = 0; t < RA; ++t) scA[t] = nxA[t];
 #pragma unroll
-        for (int t = 0; t < RB; ++t) {
-            scB[t] = nxB[t];
-            scBh[t] = scB[t] + 0x04040404u;
-        }
-        // one K step; j (the byte of the scale dwords it uses) must be a compile-time constant
+        for (int t = 0; t < RB; ++t) scB[t] = nxB[t];
+        // one K step; j (stage, register set, byte of the scale dwords) must be a compile-time constant
         auto kstep = [&](auto jc) {
             constexpr int j = decltype(jc)::value;
             constexpr int set = j & 1;
             const int64_t ks = ks4 * 4 + j;
+            const int nxt = cur + 1 == S ? 0 : cur + 1;
+            // side work of this step, in issue order: LDS reads for step ks+1, copies for step ks+S,
+            // at j == 0 the scale copies of the next group, at j == 3 the read of those scales
+            constexpr int NAUX = (NUA + NUB) + NLOAD + (j == 0 ? NSC : 0) + (j == 3 ? 1 : 0);
+            auto aux = [&](int x) {
+                if (x < NUA + NUB) { read_unit(x, nxt, std::integral_constant<int, set ^ 1>{}); return; }
+                x -= NUA + NUB;
+                if (x < NLOAD) { issue_one(x, ks + S, cur); return; }
+                x -= NLOAD;
+                if (j == 0) issue_scale_one(x, ks4 + 1, (int)((ks4 + 1) & 1));
+                if (j == 3) read_scales((int)((ks4 + 1) & 1), nxA, nxB);
+            };
             __builtin_amdgcn_sched_barrier(0);
-            // ksteps is a multiple of four: steps ks+1 and ks+2 can only be missing in the last group
-            const bool have1 = j < 3 || !last_group;
-            const bool have2 = j < 2 || !last_group;
-            if (have1) {
-                __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): this wave's copy of step ks+1 landed
-                __syncthreads();
-                if (j == 2 && have2) {                    // next group's scales, one step before their use
-#pragma unroll
-                    for (int t = 0; t < RA; ++t) nxA[t] = sA[t][(ks4 + 1) * 64];
-#pragma unroll
-                    for (int t = 0; t < RB; ++t) nxB[t] = sB[t][(ks4 + 1) * 64];
-                }
-                if (have2) issue(ks + 2, set);
-                read_frags(set ^ 1, std::integral_constant<int, set ^ 1>{});
-            }
-            __builtin_amdgcn_sched_barrier(0);            // keep the LDS reads ahead of this step's MFMAs
-            // all high-piece MFMAs first: consecutive instructions never share an accumulator
-#pragma unroll
-            for (int pa = 0; pa < PA; ++pa) {
-#pragma unroll
-                for (int pb = 0; pb < PB; ++pb) {
-#pragma unroll
-                    for (int ta = 0; ta < RA; ++ta) {
-#pragma unroll
-                        for (int tb = 0; tb < RB; ++tb) {
-                            // piece 0 of a two-piece operand is the high one: scale byte + 4
-                            const int sa = (int)((PA == 2 && pa == 0) ? scAh[ta] : scA[ta]);
-                            const int sb = (int)((PB == 2 && pb == 0) ? scBh[tb] : scB[tb]);
-                            acc[ta][tb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                operand(fa[set][ta][pa]), operand(fb[set][tb][pb]), acc[ta][tb], 2, 2, j, sa,
-                                j, sb);
-                        }
-                    }
-                }
-            }
+            // newer than D(ks+1): the data copies of the last S-2 steps, and at j == 1 the scale copies
+            // issued at the end of the previous step (at other steps they are simply awaited too)
+            wait_vmcnt<(S - 2) * NLOAD + (j == 1 ? NSC : 0)>();
+            __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
+            // one piece pair after the other: consecutive MFMAs never share an accumulator
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int tb = m % RB, ta = (m / RB) % RA, pb = (m / (RA * RB)) % PB, pa = m / (RA * RB * PB);
+                // piece 0 of a two-piece operand is the high one: scale byte + 4
+                const int sa = (int)(scA[ta] + ((PA == 2 && pa == 0) ? 0x04040404u : 0u));
+                const int sb = (int)(scB[tb] + ((PB == 2 && pb == 0) ? 0x04040404u : 0u));
+                acc[ta][tb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    operand(fa[set][ta][pa]), operand(fb[set][tb][pb]), acc[ta][tb], 2, 2, j, sa, j, sb);
+#pragma unroll
+                for (int x = m * NAUX / NM; x < (m + 1) * NAUX / NM; ++x) aux(x);
+                __builtin_amdgcn_sched_barrier(0);        // pin the interleaving as written
+            }
+            cur = nxt;
         };
         kstep(std::integral_constant<int, 0>{});
         kstep(std::integral_constant<int, 1>{});
         kstep(std::integral_constant<int, 2>{});
         kstep(std::integral_constant<int, 3>{});
     }
+    wait_vmcnt<0>();                                      // the clamped tail copies must not outlive the LDS
 
+    const int64_t rtA0 = (bm * 2 + wm) * RA, rtB0 = (bn * 2 + wn) * RB;
     float* Y = g.Y + bz * g.batch_stride_y;
     const int i = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -259,11 +302,12 @@ __global__ __launch_bounds__(256) void gemm_scaled_kernel(ScaledArgs g) {
     }
 }
 
-template <int PA, int PB, int TM, int TN>
+template <int PA, int PB, int TM, int TN, int S, int OCC>
 mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
     constexpr int UA = (PA == 2) ? 2 * TM : TM, UB = (PB == 2) ? 2 * TN : TN;
-    constexpr int smem = 2 * (UA + UB) * kUnitBytes;
-    auto kern = gemm_scaled_kernel<PA, PB, TM, TN>;
+    constexpr int smem = S * (UA + UB) * kUnitBytes + 2 * (2 * TM + 2 * TN) * 256;
+    static_assert(smem * OCC <= 160 * 1024, "LDS budget of one compute unit");
+    auto kern = gemm_scaled_kernel<PA, PB, TM, TN, S, OCC>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -272,20 +316,28 @@ mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
     }
     const int64_t tiles_m = ceil_div(g.M, 64 * TM), tiles_n = ceil_div(g.N, 64 * TN);
     if (tiles_m * tiles_n > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+    g.tiles_m = (int32_t)tiles_m;
     g.tiles_n = (int32_t)tiles_n;
-    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)batch);
+    dim3 grid((unsigned)(ceil_div(tiles_m * tiles_n, 8) * 8), (unsigned)batch);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
 
+// Tile 128 (M) x 256 (N): the left operand costs more bytes per element when it has two mantissa
+// pieces, so the tile is wider along N.  When there are at least two tiles per compute unit and
+// the stages are small enough, two workgroups share a compute unit (three stages each), so that
+// one workgroup's barrier and copy waits hide under the other's MFMAs; otherwise one workgroup
+// per compute unit runs with four stages.
 template <int PA, int PB>
 mx_status pick_tile(ScaledArgs& g, int64_t batch, hipStream_t st) {
-    // 256 x 256 tiles move the fewest bytes per MAC; fall back to 256 x 128 when that would leave
-    // most of the 256 compute units without a tile
-    const int64_t big = ceil_div(g.M, 256) * ceil_div(g.N, 256) * batch;
-    if (big >= 200) return launch_scaled<PA, PB, 4, 4>(g, batch, st);
-    return launch_scaled<PA, PB, 4, 2>(g, batch, st);
+    const int64_t tiles = ceil_div(g.M, 128) * ceil_div(g.N, 256) * batch;
+    if constexpr (PB == 1) {
+        if (tiles >= 2 * 256) return launch_scaled<PA, PB, 2, 4, 3, 2>(g, batch, st);
+        return launch_scaled<PA, PB, 2, 4, 4, 1>(g, batch, st);
+    } else {
+        return launch_scaled<PA, PB, 2, 4, 3, 1>(g, batch, st);
+    }
 }
 
 }  // namespace
@@ -301,7 +353,7 @@ mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void
     g.matrixA = ga.matrix; g.matrixB = gb.matrix; g.ldy = ldy; g.batch_stride_y = batch_stride_y;
     // pieces are stored halved (2 bits in all), mantissa units are 2^-(w-2) each
     g.eadj = 2 - (fa.mant_bits - 2) - (fb.mant_bits - 2);
-    g.tiles_n = 0;
+    g.tiles_m = g.tiles_n = 0;
     if (ga.pieces == 2 && gb.pieces == 1) return pick_tile<2, 1>(g, batch, st);
     if (ga.pieces == 1 && gb.pieces == 1) return pick_tile<1, 1>(g, batch, st);
     if (ga.pieces == 2 && gb.pieces == 2) return pick_tile<2, 2>(g, batch, st);
