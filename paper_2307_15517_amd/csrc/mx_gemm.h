@@ -21,4 +21,7 @@ mx_status gemm_block16(const GemmArgs& g, int wa, int wb, int64_t batch, hipStre
 mx_status gemm_block32(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st);
 mx_status gemm_block64(const GemmArgs& g, int wa, int wb, int64_t batch, hipStream_t st);
 
+// Decode path for M <= 4, used for M <= 2 (mx_gemv_dot.hip); MX_ERR_UNSUPPORTED when it does not apply.
+mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, hipStream_t st);
+
 }  // namespace mx

@@ -38,6 +38,10 @@ extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, con
     const int bias = (1 << (fa.exp_bits - 1)) - 1;
     g.eadj = -2 * bias - (fa.mant_bits - 2) - (fb.mant_bits - 2);
     hipStream_t st = (hipStream_t)stream;
+    if (M <= 2) {      // one or two rows: dot-product kernel; three to eight: MFMA streaming kernel
+        const mx_status s = gemv_dot(g, fa.mant_bits, fb.mant_bits, fa.block, batch, st);
+        if (s != MX_ERR_UNSUPPORTED) return s;
+    }
     switch (fa.block) {
         case 16: return gemm_block16(g, fa.mant_bits, fb.mant_bits, batch, st);
         case 32: return gemm_block32(g, fa.mant_bits, fb.mant_bits, batch, st);

@@ -249,9 +249,161 @@ __global__ __launch_bounds__(NW * 64) void gemv_fragment_kernel(GemmArgs g) {
 
 constexpr int kGemvWaves = 8;
 
+// ------------------------------------------------------------------------------------------------
+// Streaming decode kernel (M <= 8, K small enough for the activations to sit in LDS): the same
+// arithmetic as above, arranged for HBM bandwidth.  The workgroup copies the (tiny) left
+// operand's fragments into LDS once; every wave keeps D chunks of its share of the packed right
+// operand in flight in registers (a ring that is refilled as soon as a slot has been consumed),
+// so the weight stream never waits for the arithmetic.
+//   MR: rows per lane half that are computed (1 for M == 1, else 4).
+// ------------------------------------------------------------------------------------------------
+template <int WA, int WB, int B, int NW, int D, int MR>
+__global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
+    constexpr int kDwA = Piece<WA, B>::kDw, kDwB = Piece<WB, B>::kDw;
+    constexpr int kHalfDw = B / 8;
+    constexpr int XD = 16 * kDwA + 8;            // dwords kept per chunk: 16 lane pieces (rows 0..7, both halves) + 8 rows of exponents
+    extern __shared__ __attribute__((aligned(16))) uint32_t xs[];
+    float* red = reinterpret_cast<float*>(xs + g.chunks * XD);          // [NW][MR][64]
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t gb = blockIdx.x;
+    const int64_t bz = blockIdx.y;
+    const uint8_t* Abase = g.A + bz * g.matrixA;
+    const uint8_t* Bbase = g.B + bz * g.matrixB + gb * g.chunks * g.recordB;
+    const int eadj = g.eadj - Unpack<WA, B>::kScaleLog2 - Unpack<WB, B>::kScaleLog2;
+    const int chunks = (int)g.chunks;
+
+    // ring of D chunks of weights per wave; chunk number t of this wave is chunk wave + t*NW
+    uint32_t pb[D][kDwB], eb[D];
+    auto fetch = [&](int slot, int t) {
+        const int c = wave + t * NW;
+        if (c < chunks) {
+            const uint8_t* recB = Bbase + (int64_t)c * g.recordB;
+            load_dwords<kDwB>(recB + lane * (kDwB * 4), pb[slot]);
+            eb[slot] = reinterpret_cast<const uint32_t*>(recB + 64 * (kDwB * 4))[i];
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < D; ++u) fetch(u, u);
+
+    // left operand -> LDS (rows 0..7 of row group 0), in units of UD dwords, several loads in flight
+    {
+        constexpr int UD = (kDwA % 4 == 0) ? 4 : 1;          // dwords per unit
+        constexpr int UPC = XD / UD;                         // units per chunk (XD = 16*kDwA + 8)
+        constexpr int UNROLL = 4;
+        const int total = chunks * UPC;
+        for (int base = threadIdx.x; base < total; base += NW * 64 * UNROLL) {
+            uint32_t v[UNROLL][UD];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int idx = base + u * NW * 64;
+                if (idx < total) {
+                    const int c = idx / UPC, d = (idx - c * UPC) * UD;
+                    const uint8_t* rec = Abase + (int64_t)c * g.recordA;
+                    const uint8_t* src;
+                    if (d < 16 * kDwA) {
+                        const int l16 = d / kDwA, dd = d - l16 * kDwA;
+                        src = rec + ((l16 >> 3) * 32 + (l16 & 7)) * (kDwA * 4) + dd * 4;
+                    } else {
+                        src = rec + 64 * (kDwA * 4) + (d - 16 * kDwA) * 4;
+                    }
+                    load_dwords<UD>(src, v[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int idx = base + u * NW * 64;
+                if (idx < total) {
+#pragma unroll
+                    for (int d = 0; d < UD; ++d) xs[idx * UD + d] = v[u][d];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    float acc[MR];
+#pragma unroll
+    for (int r = 0; r < MR; ++r) acc[r] = 0.f;
+    const int per_wave = (chunks - wave + NW - 1) / NW;          // chunks of this wave (chunks >= NW is not required)
+    for (int t0 = 0; t0 < per_wave; t0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int t = t0 + u;
+            if (t < per_wave) {
+                const int c = wave + t * NW;
+                const uint32_t* xc = xs + c * XD;
+                uint32_t pa[kDwA], ea[4];
+                if (i < 8) {
+#pragma unroll
+                    for (int d = 0; d < kDwA; ++d) pa[d] = xc[(h * 8 + i) * kDwA + d];
+                } else {
+#pragma unroll
+                    for (int d = 0; d < kDwA; ++d) pa[d] = 0;
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ea[r] = xc[16 * kDwA + 4 * h + r];
+                uint32_t fbv[4][kHalfDw];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) Unpack<WB, B>::run(pb[u], j, fbv[j]);
+                const uint32_t ebv = eb[u];
+                fetch(u, t + D);                              // the slot is free: refill it
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t fa[kHalfDw];
+                    Unpack<WA, B>::run(pa, j, fa);
+                    const v16i d = block_mfma<B>(fa, fbv[j]);
+                    const int ebj = (int)((ebv >> (8 * j)) & 0xFFu) + eadj;
+#pragma unroll
+                    for (int r = 0; r < MR; ++r) {
+                        const int e = (int)((ea[r] >> (8 * j)) & 0xFFu) + ebj;
+                        acc[r] += __builtin_ldexpf((float)d[r], e);
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < MR; ++r) red[(wave * MR + r) * 64 + lane] = acc[r];
+    __syncthreads();
+    for (int t = threadIdx.x; t < MR * 64; t += NW * 64) {
+        const int r = t >> 6, l = t & 63;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += red[(w * MR + r) * 64 + l];
+        const int64_t m = 4 * (l >> 5) + r;
+        const int64_t n = gb * 32 + (l & 31);
+        if (m < g.M && n < g.N) g.Y[bz * g.batch_stride_y + m * g.ldy + n] = s;
+    }
+}
+
+constexpr int kStreamWaves = 8, kStreamDepth = 8;
+
+template <int WA, int WB, int B, int MR>
+mx_status launch_stream(const GemmArgs& g, int64_t batch, size_t smem, hipStream_t st) {
+    auto kern = gemv_stream_kernel<WA, WB, B, kStreamWaves, kStreamDepth, MR>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return MX_ERR_DEVICE;
+        configured = true;
+    }
+    dim3 grid((unsigned)g.groupsB, (unsigned)batch);
+    hipLaunchKernelGGL(kern, grid, dim3(kStreamWaves * 64), smem, st, g);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
 template <int WA, int WB, int B>
 mx_status launch(const GemmArgs& g, int64_t batch, hipStream_t st) {
     if (g.M <= 8) {
+        // streaming kernel when the left operand fits in LDS next to the reduction buffer
+        constexpr int XD = 16 * Piece<WA, B>::kDw + 8;
+        const size_t smem = (size_t)g.chunks * XD * 4 + (size_t)kStreamWaves * 4 * 64 * 4;
+        if (g.chunks > 0 && g.chunks < (1 << 20) && smem <= 160 * 1024) {
+            if (g.M == 1) return launch_stream<WA, WB, B, 1>(g, batch, smem, st);
+            return launch_stream<WA, WB, B, 4>(g, batch, smem, st);
+        }
         dim3 grid((unsigned)g.groupsB, (unsigned)batch);
         hipLaunchKernelGGL((gemv_fragment_kernel<WA, WB, B, kGemvWaves>), grid, dim3(kGemvWaves * 64), 0, st, g);
     } else {

@@ -1,0 +1,260 @@
+// Decode kernel for very few activation rows (M <= 4), right operand in the fragment layout.
+//
+// Arithmetic as in the MFMA kernels (Section 3.2 of the paper: exact integer block dots, the two
+// shared exponents applied once per block), but the dots are taken with v_dot4_i32_i8: with one
+// to four rows the 32x32 MFMA would spend three quarters of its work, and all of its epilogue,
+// on rows that do not exist, and the kernel is bound by instruction issue, not by the matrix
+// cores.  Lane 32*h + i owns output column 32*gb + i and half h of every block (that is what the
+// fragment layout gives it); it adds scale * half-dot into its own fp32 partial sums, and the two
+// halves of a column meet in one cross-lane add at the end.  The activations are unpacked to int8
+// once per workgroup into LDS and read back as broadcasts.
+#include "mx_gemm.h"
+
+namespace mx {
+namespace {
+
+template <int W, int B> struct Piece { static constexpr int kDw = B * W / 16; };
+
+template <int NDW>
+__device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t* out) {
+    if constexpr (NDW % 4 == 0) {
+#pragma unroll
+        for (int d = 0; d < NDW / 4; ++d) {
+            uint4 v = reinterpret_cast<const uint4*>(p)[d];
+            out[4 * d] = v.x; out[4 * d + 1] = v.y; out[4 * d + 2] = v.z; out[4 * d + 3] = v.w;
+        }
+    } else if constexpr (NDW % 2 == 0) {
+#pragma unroll
+        for (int d = 0; d < NDW / 2; ++d) {
+            uint2 v = reinterpret_cast<const uint2*>(p)[d];
+            out[2 * d] = v.x; out[2 * d + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < NDW; ++d) out[d] = reinterpret_cast<const uint32_t*>(p)[d];
+    }
+}
+
+// Half-block j of a lane piece of the right operand -> B/2 int8 in B/8 dwords (times 16 for W = 4).
+template <int W, int B> struct UnpackB {
+    static constexpr int kScaleLog2 = (W == 4) ? 4 : 0;
+    __device__ __forceinline__ static void run(const uint32_t* piece, int j, uint32_t* out) {
+        constexpr int kOut = B / 8;
+        if constexpr (W == 8) {
+#pragma unroll
+            for (int d = 0; d < kOut; ++d) out[d] = piece[j * kOut + d];
+        } else if constexpr (W == 4) {
+#pragma unroll
+            for (int d = 0; d < kOut / 2; ++d) {
+                const uint32_t x = piece[j * (kOut / 2) + d];
+                out[2 * d] = (x << 4) & 0xF0F0F0F0u;
+                out[2 * d + 1] = x & 0xF0F0F0F0u;
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < kOut; ++d) {
+                uint32_t o = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int bit = (j * (B / 2) + d * 4 + t) * W;
+                    o |= ((uint32_t)stream_get<W>(piece, bit) & 0xFFu) << (8 * t);
+                }
+                out[d] = o;
+            }
+        }
+    }
+};
+
+// Mantissa t of half-block j of a left-operand lane piece (runtime width), sign-extended.
+__device__ __forceinline__ int piece_get(const uint8_t* piece, int j, int t, int w, int B) {
+    int pos = j * (B / 2) + t;
+    if (w == 4) {                        // nibbles of every group of 8 are stored e0 e4 e1 e5 e2 e6 e3 e7
+        const int t8 = t & 7;
+        pos = j * (B / 2) + (t & ~7) + (t8 < 4 ? 2 * t8 : 2 * (t8 - 4) + 1);
+    }
+    const int bit = pos * w, sh = bit & 7;
+    uint32_t v = piece[bit >> 3];
+    if (sh + w > 8) v |= (uint32_t)piece[(bit >> 3) + 1] << 8;
+    v >>= sh;
+    return ((int)(v << (32 - w))) >> (32 - w);
+}
+
+struct DotArgs {
+    GemmArgs g;
+    int32_t wa;          // stored width of the left operand
+};
+
+// MP: rows computed (1, 2 or 4; M <= MP, missing rows are fed zeros).  NW waves per workgroup, each
+// keeping a ring of D chunks of weights in flight.
+template <int WB, int B, int MP, int NW, int D>
+__global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
+    const GemmArgs& g = a.g;
+    constexpr int kDwB = Piece<WB, B>::kDw;
+    constexpr int kHalfDw = B / 8;               // int8 dwords of a half block
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds[];
+    const int chunks = (int)g.chunks;
+    // LDS: x8[MP][chunks*4 blocks][2 halves][kHalfDw dwords], xe[MP][chunks] exponent dwords, red[NW][MP][64]
+    uint32_t* x8 = lds;
+    uint32_t* xe = x8 + MP * chunks * 4 * 2 * kHalfDw;
+    float* red = reinterpret_cast<float*>(xe + MP * chunks);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t gb = blockIdx.x;
+    const int64_t bz = blockIdx.y;
+    const uint8_t* Abase = g.A + bz * g.matrixA;
+    const uint8_t* Bbase = g.B + bz * g.matrixB + gb * g.chunks * g.recordB;
+    const int eadj = g.eadj - UnpackB<WB, B>::kScaleLog2;
+    const int pieceA = B * a.wa / 4;             // bytes of a left-operand lane piece
+
+    uint32_t pb[D][kDwB], eb[D];
+    auto fetch = [&](int slot, int t) {
+        const int c = wave + t * NW;
+        if (c < chunks) {
+            const uint8_t* recB = Bbase + (int64_t)c * g.recordB;
+            load_dwords<kDwB>(recB + lane * (kDwB * 4), pb[slot]);
+            eb[slot] = reinterpret_cast<const uint32_t*>(recB + 64 * (kDwB * 4))[i];
+        }
+    };
+#pragma unroll
+    for (int u = 0; u < D; ++u) fetch(u, u);
+
+    // activations -> int8 in LDS: one item per (row, chunk, half)
+    for (int idx = threadIdx.x; idx < MP * chunks * 2; idx += NW * 64) {
+        const int hh = idx & 1, c = (idx >> 1) % chunks, m = (idx >> 1) / chunks;
+        const uint8_t* rec = Abase + (int64_t)c * g.recordA;
+        const uint8_t* piece = rec + (32 * hh + m) * pieceA;
+        uint32_t* dst = x8 + ((m * chunks + c) * 4 * 2 + hh) * kHalfDw;      // + j*2*kHalfDw per block
+        if (m < g.M) {
+            if (a.wa == 8) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int d = 0; d < kHalfDw; ++d)
+                        dst[j * 2 * kHalfDw + d] = reinterpret_cast<const uint32_t*>(piece)[j * kHalfDw + d];
+            } else {
+                for (int j = 0; j < 4; ++j)
+                    for (int d = 0; d < kHalfDw; ++d) {
+                        uint32_t o = 0;
+                        for (int t = 0; t < 4; ++t)
+                            o |= ((uint32_t)piece_get(piece, j, d * 4 + t, a.wa, B) & 0xFFu) << (8 * t);
+                        dst[j * 2 * kHalfDw + d] = o;
+                    }
+            }
+            if (hh == 0) xe[m * chunks + c] = reinterpret_cast<const uint32_t*>(rec + 64 * pieceA)[m];
+        } else {
+            for (int j = 0; j < 4; ++j)
+                for (int d = 0; d < kHalfDw; ++d) dst[j * 2 * kHalfDw + d] = 0;
+            if (hh == 0) xe[m * chunks + c] = 0;
+        }
+    }
+    __syncthreads();
+
+    float acc[MP];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) acc[m] = 0.f;
+    const int per_wave = (chunks - wave + NW - 1) / NW;
+    for (int t0 = 0; t0 < per_wave; t0 += D) {
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            const int t = t0 + u;
+            if (t < per_wave) {
+                const int c = wave + t * NW;
+                uint32_t fb[4][kHalfDw];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) UnpackB<WB, B>::run(pb[u], j, fb[j]);
+                const uint32_t ebv = eb[u];
+                fetch(u, t + D);                                  // the slot is free: refill it
+                uint32_t exm[MP];
+#pragma unroll
+                for (int m = 0; m < MP; ++m) exm[m] = xe[m * chunks + c];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ebj = (int)((ebv >> (8 * j)) & 0xFFu) + eadj;
+#pragma unroll
+                    for (int m = 0; m < MP; ++m) {
+                        const uint32_t* xv = x8 + (((m * chunks + c) * 4 + j) * 2 + h) * kHalfDw;
+                        int d = 0;
+#pragma unroll
+                        for (int q = 0; q < kHalfDw; ++q) d = __builtin_amdgcn_sdot4((int)fb[j][q], (int)xv[q], d, false);
+                        const int e = (int)((exm[m] >> (8 * j)) & 0xFFu) + ebj;
+                        acc[m] += __builtin_ldexpf((float)d, e);
+                    }
+                }
+            }
+        }
+    }
+    // the two halves of a column, then the waves
+#pragma unroll
+    for (int m = 0; m < MP; ++m) {
+        acc[m] += __shfl_xor(acc[m], 32, 64);
+        if (h == 0) red[(wave * MP + m) * 32 + i] = acc[m];
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < MP * 32; t += NW * 64) {
+        const int m = t >> 5, col = t & 31;
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += red[(w * MP + m) * 32 + col];
+        const int64_t n = gb * 32 + col;
+        if (m < g.M && n < g.N) g.Y[bz * g.batch_stride_y + (int64_t)m * g.ldy + n] = s;
+    }
+}
+
+constexpr int kDotWaves = 8, kDotDepth = 8;
+
+template <int WB, int B, int MP>
+mx_status launch_dot(const DotArgs& a, int64_t batch, hipStream_t st) {
+    const size_t smem = ((size_t)MP * a.g.chunks * 4 * 2 * (B / 8) + (size_t)MP * a.g.chunks) * 4 +
+                        (size_t)kDotWaves * MP * 32 * 4;
+    if (smem > 160 * 1024) return MX_ERR_UNSUPPORTED;
+    auto kern = gemv_dot_kernel<WB, B, MP, kDotWaves, kDotDepth>;
+    static bool configured = false;
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return MX_ERR_DEVICE;
+        configured = true;
+    }
+    dim3 grid((unsigned)a.g.groupsB, (unsigned)batch);
+    hipLaunchKernelGGL(kern, grid, dim3(kDotWaves * 64), smem, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+template <int B, int MP>
+mx_status dispatch_wb(const DotArgs& a, int wb, int64_t batch, hipStream_t st) {
+    switch (wb) {
+        case 2: return launch_dot<2, B, MP>(a, batch, st);
+        case 3: return launch_dot<3, B, MP>(a, batch, st);
+        case 4: return launch_dot<4, B, MP>(a, batch, st);
+        case 5: return launch_dot<5, B, MP>(a, batch, st);
+        case 6: return launch_dot<6, B, MP>(a, batch, st);
+        case 7: return launch_dot<7, B, MP>(a, batch, st);
+        case 8: return launch_dot<8, B, MP>(a, batch, st);
+    }
+    return MX_ERR_BAD_ARG;
+}
+
+template <int B>
+mx_status dispatch_m(const DotArgs& a, int wb, int64_t batch, hipStream_t st) {
+    if (a.g.M == 1) return dispatch_wb<B, 1>(a, wb, batch, st);
+    if (a.g.M == 2) return dispatch_wb<B, 2>(a, wb, batch, st);
+    return dispatch_wb<B, 4>(a, wb, batch, st);
+}
+
+}  // namespace
+
+// M <= 4.  MX_ERR_UNSUPPORTED when the activations do not fit in LDS (the caller falls back).
+mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, hipStream_t st) {
+    DotArgs a;
+    a.g = g;
+    a.wa = wa;
+    if (g.chunks <= 0) return MX_ERR_UNSUPPORTED;
+    switch (block) {
+        case 16: return dispatch_m<16>(a, wb, batch, st);
+        case 32: return dispatch_m<32>(a, wb, batch, st);
+        case 64: return dispatch_m<64>(a, wb, batch, st);
+    }
+    return MX_ERR_UNSUPPORTED;
+}
+
+}  // namespace mx

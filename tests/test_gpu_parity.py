@@ -264,6 +264,22 @@ def test_linear_equals_quantize_pack_gemm(M):
     assert torch.equal(y1, y2)            # same arithmetic in the same order: identical bits
 
 
+@pytest.mark.parametrize("M,K,block", [(3, 300 * 64, 16), (8, 270 * 128, 32), (1, 64, 16), (2, 5 * 256, 64)])
+def test_gemv_long_and_short_k(M, K, block):
+    """Decode path beyond what the streaming kernel keeps in LDS (falls back to the looping kernel),
+    and at a single chunk."""
+    rng = np.random.default_rng(K + M)
+    N = 70
+    qa, ea = random_operand(rng, M, K, block, 8, 118, 132)
+    qb, eb = random_operand(rng, N, K, block, 4, 118, 132)
+    A, fa = gpu_operand(qa, ea, block, 8)
+    B, fb = gpu_operand(qb, eb, block, 4)
+    y = mx.gemm(A, fa, B, fb, M, N, K)
+    torch.cuda.synchronize()
+    y_ref, mag = orc.gemm(qa, ea, 8, qb, eb, 4, block, want_mag=True)
+    check_product(host(y)[0], y_ref, mag, "gemv M=%d K=%d block=%d" % (M, K, block))
+
+
 def random_operand(rng, rows, K, block, w, elo, ehi):
     qmax = 2 ** (w - 1) - 1
     q = rng.integers(-qmax - 1, qmax + 1, size=(rows, K)).astype(np.int8)     # includes the code -2^(w-1)
