@@ -144,9 +144,12 @@ __global__ __launch_bounds__(256) void unpack_matrix_kernel(MatPackArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// fp32 -> layout in one pass.  One wave per (row tile, group of four K steps): 32 rows x 256
-// floats, read one full 1 KiB row segment per instruction, turned through LDS so that each lane
-// ends up with the 32 consecutive elements of its row that it has to emit.
+// fp32 -> layout in one pass.  One workgroup of four waves per (row tile, group of four K steps);
+// wave j owns K step j of the group: 32 rows x 64 floats, read as 256-byte row segments (four
+// rows per load instruction), turned through LDS so that each lane ends up with the 32
+// consecutive elements of its row that it has to emit.  Small work items keep several waves per
+// SIMD resident, so the arithmetic of the waves whose data has arrived overlaps the loads that are
+// still in flight.
 // ------------------------------------------------------------------------------------------------
 struct QPackArgs {
     const float* x;
@@ -156,103 +159,106 @@ struct QPackArgs {
     int32_t bias, emax;
 };
 
-constexpr int kQpRowPitch = 1024 + 16;    // bytes; the 16-byte skew spreads the lanes' rows over the banks
+constexpr int kQpRowPitch = 256 + 16;     // bytes; the 16-byte skew spreads the lanes' rows over the banks
 
 template <int W, int B, int RND>
-__global__ __launch_bounds__(64) void quantize_pack_matrix_kernel(QPackArgs a) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[32 * kQpRowPitch];
+__global__ __launch_bounds__(256) void quantize_pack_matrix_kernel(QPackArgs a) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 32 * kQpRowPitch];
+    __shared__ uint32_t scale_bytes[4][64];
     constexpr int P = (W <= 4) ? 1 : 2;
     constexpr float qmax = (float)((1 << (W - 1)) - 1);
-    const int lane = threadIdx.x;
+    const int j = threadIdx.x >> 6, lane = threadIdx.x & 63;        // j: K step of the group
+    uint8_t* lds = lds_all + j * 32 * kQpRowPitch;
     const int i = lane & 31, h = lane >> 5;
     const int64_t ks4n = a.g.ksteps / 4;
     const int64_t rt = blockIdx.x / ks4n, ks4 = blockIdx.x - rt * ks4n;
     const int64_t b = blockIdx.y;
     const float* xb = a.x + b * a.batch_stride;
-    const int64_t col0 = ks4 * 256;
+    const int64_t ks = ks4 * 4 + j;
 
-    // 32 rows x 1 KiB, zero outside the matrix
-    float4 in[32];
-    const int64_t c = col0 + lane * 4;
+    // 32 rows x 256 bytes, zero outside the matrix: instruction r covers rows 4r .. 4r+3
+    float4 in[8];
+    const int64_t c = ks * 64 + (lane & 15) * 4;
 #pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        const int64_t row = rt * 32 + r;
+    for (int r = 0; r < 8; ++r) {
+        const int64_t row = rt * 32 + 4 * r + (lane >> 4);
         in[r] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row < a.rows && c < a.cols) in[r] = *reinterpret_cast<const float4*>(xb + row * a.row_stride + c);
     }
 #pragma unroll
-    for (int r = 0; r < 32; ++r) *reinterpret_cast<float4*>(lds + r * kQpRowPitch + lane * 16) = in[r];
+    for (int r = 0; r < 8; ++r)
+        *reinterpret_cast<float4*>(lds + (4 * r + (lane >> 4)) * kQpRowPitch + (lane & 15) * 16) = in[r];
     __builtin_amdgcn_wave_barrier();
 
     uint8_t* base = a.packed + b * a.g.matrix;
-    uint32_t scale_dword = 0;
-#pragma unroll 1
-    for (int j = 0; j < 4; ++j) {
-        const int64_t ks = ks4 * 4 + j;
-        float v[32];
-        const uint8_t* src = lds + i * kQpRowPitch + j * 256 + h * 128;
+    float v[32];
+    const uint8_t* src = lds + i * kQpRowPitch + h * 128;
 #pragma unroll
-        for (int q4 = 0; q4 < 8; ++q4) {
-            const float4 t = *reinterpret_cast<const float4*>(src + q4 * 16);
-            v[4 * q4] = t.x; v[4 * q4 + 1] = t.y; v[4 * q4 + 2] = t.z; v[4 * q4 + 3] = t.w;
-        }
-        uint32_t am = 0;
-#pragma unroll
-        for (int e = 0; e < 32; ++e) {
-            const uint32_t ab = __float_as_uint(v[e]) & 0x7fffffffu;
-            am = ab > am ? ab : am;
-        }
-        if (B == 64) {                      // the two halves of a lane pair form one block
-            const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
-            am = o > am ? o : am;
-        }
-        const int ef = (int)(am >> 23);
-        int E = ef == 0 ? -127 : ef - 127;
-        E = E < -a.bias ? -a.bias : E;
-        E = E > a.emax ? a.emax : E;
-        const int shift = (W - 2) - E;
-        v16f lo0, lo1, hi0, hi1;
-#pragma unroll
-        for (int e = 0; e < 32; ++e) {
-            float s = __builtin_ldexpf(v[e], shift);
-            float r = RND == MX_RNE ? __builtin_rintf(s) : __builtin_truncf(s);
-            r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
-            float hi = 0.f, lo = r;
-            if (P == 2) {
-                hi = __builtin_floorf(r * 0.0625f + 0.5f);      // h = floor((q + 8) / 16)
-                lo = r - 16.f * hi;
-            }
-            lo += 0.0f;                                          // -0.0 (a small negative rounded to zero) -> +0.0
-            // the packing instruction interleaves its two sources: element 2t from the first, 2t+1 from the second
-            if (e & 1) { lo1[e >> 1] = lo; hi1[e >> 1] = hi; }
-            else       { lo0[e >> 1] = lo; hi0[e >> 1] = hi; }
-        }
-        const v6i fl = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(lo0, lo1, 2.0f);   // codes of piece / 2
-        uint8_t* unit = base + mat_unit(a.g, P == 2 ? rt : rt >> 1, ks);
-        const int lslot = P == 2 ? 1 : (int)(rt & 1);
-        *reinterpret_cast<uint4*>(unit + frag_lo(lslot, lane)) =
-            make_uint4((uint32_t)fl[0], (uint32_t)fl[1], (uint32_t)fl[2], (uint32_t)fl[3]);
-        *reinterpret_cast<uint2*>(unit + frag_hi(lslot, lane)) = make_uint2((uint32_t)fl[4], (uint32_t)fl[5]);
-        if (P == 2) {
-            const v6i fh = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(hi0, hi1, 2.0f);
-            *reinterpret_cast<uint4*>(unit + frag_lo(0, lane)) =
-                make_uint4((uint32_t)fh[0], (uint32_t)fh[1], (uint32_t)fh[2], (uint32_t)fh[3]);
-            *reinterpret_cast<uint2*>(unit + frag_hi(0, lane)) = make_uint2((uint32_t)fh[4], (uint32_t)fh[5]);
-        }
-        const bool inside = (rt * 32 + i) < a.rows && (ks * 64 + h * 32) < a.cols;
-        const uint32_t sb = inside ? (uint32_t)(E + 127) : 0u;      // E + bias + (127 - bias)
-        scale_dword |= sb << (8 * j);
+    for (int q4 = 0; q4 < 8; ++q4) {
+        const float4 t = *reinterpret_cast<const float4*>(src + q4 * 16);
+        v[4 * q4] = t.x; v[4 * q4 + 1] = t.y; v[4 * q4 + 2] = t.z; v[4 * q4 + 3] = t.w;
     }
-    *reinterpret_cast<uint32_t*>(base + a.g.frag_bytes + ((rt * ks4n + ks4) * 64 + lane) * 4) = scale_dword;
+    uint32_t am = 0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const uint32_t ab = __float_as_uint(v[e]) & 0x7fffffffu;
+        am = ab > am ? ab : am;
+    }
+    if (B == 64) {                      // the two halves of a lane pair form one block
+        const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
+        am = o > am ? o : am;
+    }
+    const int ef = (int)(am >> 23);
+    int E = ef == 0 ? -127 : ef - 127;
+    E = E < -a.bias ? -a.bias : E;
+    E = E > a.emax ? a.emax : E;
+    const int shift = (W - 2) - E;
+    v16f lo0, lo1, hi0, hi1;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        float s = __builtin_ldexpf(v[e], shift);
+        float r = RND == MX_RNE ? __builtin_rintf(s) : __builtin_truncf(s);
+        r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+        float hi = 0.f, lo = r;
+        if (P == 2) {
+            hi = __builtin_floorf(r * 0.0625f + 0.5f);      // h = floor((q + 8) / 16)
+            lo = r - 16.f * hi;
+        }
+        lo += 0.0f;                                          // -0.0 (a small negative rounded to zero) -> +0.0
+        // the packing instruction interleaves its two sources: element 2t from the first, 2t+1 from the second
+        if (e & 1) { lo1[e >> 1] = lo; hi1[e >> 1] = hi; }
+        else       { lo0[e >> 1] = lo; hi0[e >> 1] = hi; }
+    }
+    const v6i fl = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(lo0, lo1, 2.0f);   // codes of piece / 2
+    uint8_t* unit = base + mat_unit(a.g, P == 2 ? rt : rt >> 1, ks);
+    const int lslot = P == 2 ? 1 : (int)(rt & 1);
+    *reinterpret_cast<uint4*>(unit + frag_lo(lslot, lane)) =
+        make_uint4((uint32_t)fl[0], (uint32_t)fl[1], (uint32_t)fl[2], (uint32_t)fl[3]);
+    *reinterpret_cast<uint2*>(unit + frag_hi(lslot, lane)) = make_uint2((uint32_t)fl[4], (uint32_t)fl[5]);
+    if (P == 2) {
+        const v6i fh = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(hi0, hi1, 2.0f);
+        *reinterpret_cast<uint4*>(unit + frag_lo(0, lane)) =
+            make_uint4((uint32_t)fh[0], (uint32_t)fh[1], (uint32_t)fh[2], (uint32_t)fh[3]);
+        *reinterpret_cast<uint2*>(unit + frag_hi(0, lane)) = make_uint2((uint32_t)fh[4], (uint32_t)fh[5]);
+    }
+    // the four waves' scale bytes of a lane make one dword
+    const bool inside = (rt * 32 + i) < a.rows && (ks * 64 + h * 32) < a.cols;
+    scale_bytes[j][lane] = inside ? (uint32_t)(E + 127) : 0u;          // E + bias + (127 - bias)
+    __syncthreads();
+    if (j == 0) {
+        const uint32_t d = scale_bytes[0][lane] | (scale_bytes[1][lane] << 8) | (scale_bytes[2][lane] << 16) |
+                           (scale_bytes[3][lane] << 24);
+        *reinterpret_cast<uint32_t*>(base + a.g.frag_bytes + ((rt * ks4n + ks4) * 64 + lane) * 4) = d;
+    }
 }
 
 template <int W, int B>
 mx_status launch_qpack(const QPackArgs& a, int64_t batch, int rnd, hipStream_t st) {
     dim3 grid((unsigned)(a.g.row_tiles * (a.g.ksteps / 4)), (unsigned)batch);
     if (rnd == MX_RNE)
-        hipLaunchKernelGGL((quantize_pack_matrix_kernel<W, B, MX_RNE>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((quantize_pack_matrix_kernel<W, B, MX_RNE>), grid, dim3(256), 0, st, a);
     else
-        hipLaunchKernelGGL((quantize_pack_matrix_kernel<W, B, MX_RTZ>), grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL((quantize_pack_matrix_kernel<W, B, MX_RTZ>), grid, dim3(256), 0, st, a);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
