@@ -167,7 +167,8 @@ MX_API mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const v
  * on the fly (same arithmetic as mx_quantize, axis 1), then the product above
  * against B_packed [N x K].  The result equals mx_quantize + mx_pack + mx_gemm.
  * A_scratch: device buffer of mx_packed_bytes(1, M, K, fx, layout) bytes, 256-byte
- * aligned, that receives the packed activations (caller-owned, may be reused).
+ * aligned, for the packed activations (caller-owned, may be reused; its content after the call is
+ * unspecified: for one or two rows the kernel quantizes straight into on-chip memory).
  */
 MX_API mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
                     void* A_scratch, const void* B_packed, int64_t N, mx_format fb, int32_t layout,

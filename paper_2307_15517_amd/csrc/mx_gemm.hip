@@ -7,6 +7,24 @@ mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void
                       mx_format fb, float* Y, int64_t ldy, int64_t batch_stride_y, hipStream_t st);
 }  // namespace mx
 
+namespace mx {
+GemmArgs fragment_args(int64_t M, int64_t N, int64_t K, const void* A, mx_format fa, const void* B, mx_format fb,
+                       float* Y, int64_t ldy, int64_t batch_stride_y) {
+    const FragGeom ga = frag_geom(M, K, fa.block, fa.mant_bits);
+    const FragGeom gb = frag_geom(N, K, fb.block, fb.mant_bits);
+    GemmArgs g;
+    g.A = (const uint8_t*)A; g.B = (const uint8_t*)B; g.Y = Y;
+    g.M = M; g.N = N; g.K = K;
+    g.groupsA = ga.groups; g.groupsB = gb.groups; g.chunks = ga.chunks;
+    g.matrixA = ga.matrix; g.matrixB = gb.matrix;
+    g.ldy = ldy; g.batch_stride_y = batch_stride_y;
+    g.recordA = ga.record; g.recordB = gb.record;
+    const int bias = (1 << (fa.exp_bits - 1)) - 1;
+    g.eadj = -2 * bias - (fa.mant_bits - 2) - (fb.mant_bits - 2);
+    return g;
+}
+}  // namespace mx
+
 using namespace mx;
 
 extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed,
@@ -26,17 +44,8 @@ extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, con
     if (layout == MX_LAYOUT_MATRIX)
         return gemm_scaled(batch, M, N, K, A_packed, fa, B_packed, fb, Y, ldy, batch_stride_y, (hipStream_t)stream);
     const FragGeom ga = frag_geom(M, K, fa.block, fa.mant_bits);
-    const FragGeom gb = frag_geom(N, K, fb.block, fb.mant_bits);
     if (ceil_div(ga.groups, 4) > 65535) return MX_ERR_UNSUPPORTED;
-    GemmArgs g;
-    g.A = (const uint8_t*)A_packed; g.B = (const uint8_t*)B_packed; g.Y = Y;
-    g.M = M; g.N = N;
-    g.groupsA = ga.groups; g.groupsB = gb.groups; g.chunks = ga.chunks;
-    g.matrixA = ga.matrix; g.matrixB = gb.matrix;
-    g.ldy = ldy; g.batch_stride_y = batch_stride_y;
-    g.recordA = ga.record; g.recordB = gb.record;
-    const int bias = (1 << (fa.exp_bits - 1)) - 1;
-    g.eadj = -2 * bias - (fa.mant_bits - 2) - (fb.mant_bits - 2);
+    const GemmArgs g = fragment_args(M, N, K, A_packed, fa, B_packed, fb, Y, ldy, batch_stride_y);
     hipStream_t st = (hipStream_t)stream;
     if (M <= 2) {      // one or two rows: dot-product kernel; three to eight: MFMA streaming kernel
         const mx_status s = gemv_dot(g, fa.mant_bits, fb.mant_bits, fa.block, batch, st);

@@ -377,11 +377,11 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
     }
 }
 
-constexpr int kStreamWaves = 8, kStreamDepth = 8;
+constexpr int kStreamDepth = 8;
 
-template <int WA, int WB, int B, int MR>
+template <int WA, int WB, int B, int MR, int NW>
 mx_status launch_stream(const GemmArgs& g, int64_t batch, size_t smem, hipStream_t st) {
-    auto kern = gemv_stream_kernel<WA, WB, B, kStreamWaves, kStreamDepth, MR>;
+    auto kern = gemv_stream_kernel<WA, WB, B, NW, kStreamDepth, MR>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -389,7 +389,7 @@ mx_status launch_stream(const GemmArgs& g, int64_t batch, size_t smem, hipStream
         configured = true;
     }
     dim3 grid((unsigned)g.groupsB, (unsigned)batch);
-    hipLaunchKernelGGL(kern, grid, dim3(kStreamWaves * 64), smem, st, g);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, g);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
@@ -397,12 +397,18 @@ mx_status launch_stream(const GemmArgs& g, int64_t batch, size_t smem, hipStream
 template <int WA, int WB, int B>
 mx_status launch(const GemmArgs& g, int64_t batch, hipStream_t st) {
     if (g.M <= 8) {
-        // streaming kernel when the left operand fits in LDS next to the reduction buffer
+        // streaming kernel when the left operand fits in LDS next to the reduction buffer; 16 waves per
+        // workgroup when there are too few column groups to fill the chip with 8
         constexpr int XD = 16 * Piece<WA, B>::kDw + 8;
-        const size_t smem = (size_t)g.chunks * XD * 4 + (size_t)kStreamWaves * 4 * 64 * 4;
+        const int nw = g.groupsB * batch < 256 ? 16 : 8;
+        const size_t smem = (size_t)g.chunks * XD * 4 + (size_t)nw * 4 * 64 * 4;
         if (g.chunks > 0 && g.chunks < (1 << 20) && smem <= 160 * 1024) {
-            if (g.M == 1) return launch_stream<WA, WB, B, 1>(g, batch, smem, st);
-            return launch_stream<WA, WB, B, 4>(g, batch, smem, st);
+            if (nw == 16) {
+                if (g.M == 1) return launch_stream<WA, WB, B, 1, 16>(g, batch, smem, st);
+                return launch_stream<WA, WB, B, 4, 16>(g, batch, smem, st);
+            }
+            if (g.M == 1) return launch_stream<WA, WB, B, 1, 8>(g, batch, smem, st);
+            return launch_stream<WA, WB, B, 4, 8>(g, batch, smem, st);
         }
         dim3 grid((unsigned)g.groupsB, (unsigned)batch);
         hipLaunchKernelGGL((gemv_fragment_kernel<WA, WB, B, kGemvWaves>), grid, dim3(kGemvWaves * 64), 0, st, g);

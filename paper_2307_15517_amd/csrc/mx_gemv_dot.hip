@@ -82,6 +82,10 @@ __device__ __forceinline__ int piece_get(const uint8_t* piece, int j, int t, int
 struct DotArgs {
     GemmArgs g;
     int32_t wa;          // stored width of the left operand
+    // fused form (mx_linear): the left operand is still fp32 and is quantized on the way into LDS
+    const float* x;      // null: take the packed left operand g.A
+    int64_t x_stride;
+    int32_t bias, emax, rounding;
 };
 
 // MP: rows computed (1, 2 or 4; M <= MP, missing rows are fed zeros).  NW waves per workgroup, each
@@ -118,7 +122,53 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
 #pragma unroll
     for (int u = 0; u < D; ++u) fetch(u, u);
 
-    // activations -> int8 in LDS: one item per (row, chunk, half)
+    if (a.x != nullptr) {
+        // fp32 activations -> MXInt (the arithmetic of mx_quantize) -> int8 in LDS: one item per (row, block)
+        const int nblk = (int)(g.K / B);
+        const float qmax = (float)((1 << (a.wa - 1)) - 1);
+        for (int idx = threadIdx.x; idx < MP * chunks * 4; idx += NW * 64) {
+            const int blk = idx % (chunks * 4), m = idx / (chunks * 4);
+            uint32_t* dst = x8 + (m * chunks * 4 + blk) * 2 * kHalfDw;
+            uint32_t out[2 * kHalfDw];
+            int ebyte = 0;
+            if (m < g.M && blk < nblk) {
+                float v[B];
+                const float* src = a.x + (int64_t)m * a.x_stride + (int64_t)blk * B;
+                uint32_t am = 0;
+#pragma unroll
+                for (int k = 0; k < B; ++k) {
+                    v[k] = src[k];
+                    const uint32_t ab = __float_as_uint(v[k]) & 0x7fffffffu;
+                    am = ab > am ? ab : am;
+                }
+                const int ef = (int)(am >> 23);
+                int E = ef == 0 ? -127 : ef - 127;
+                E = E < -a.bias ? -a.bias : E;
+                E = E > a.emax ? a.emax : E;
+                const int shift = (a.wa - 2) - E;
+#pragma unroll
+                for (int d = 0; d < 2 * kHalfDw; ++d) {
+                    uint32_t o = 0;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float sc = __builtin_ldexpf(v[4 * d + t], shift);
+                        float r = a.rounding == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
+                        r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+                        o |= ((uint32_t)(int)r & 0xFFu) << (8 * t);
+                    }
+                    out[d] = o;
+                }
+                ebyte = E + a.bias;
+            } else {
+#pragma unroll
+                for (int d = 0; d < 2 * kHalfDw; ++d) out[d] = 0;
+            }
+#pragma unroll
+            for (int d = 0; d < 2 * kHalfDw; ++d) dst[d] = out[d];
+            reinterpret_cast<uint8_t*>(xe)[(m * chunks + (blk >> 2)) * 4 + (blk & 3)] = (uint8_t)ebyte;
+        }
+    } else {
+    // packed activations -> int8 in LDS: one item per (row, chunk, half)
     for (int idx = threadIdx.x; idx < MP * chunks * 2; idx += NW * 64) {
         const int hh = idx & 1, c = (idx >> 1) % chunks, m = (idx >> 1) / chunks;
         const uint8_t* rec = Abase + (int64_t)c * g.recordA;
@@ -146,6 +196,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
                 for (int d = 0; d < kHalfDw; ++d) dst[j * 2 * kHalfDw + d] = 0;
             if (hh == 0) xe[m * chunks + c] = 0;
         }
+    }
     }
     __syncthreads();
 
@@ -200,14 +251,16 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
     }
 }
 
-constexpr int kDotWaves = 8, kDotDepth = 8;
+constexpr int kDotDepth = 8;
 
-template <int WB, int B, int MP>
-mx_status launch_dot(const DotArgs& a, int64_t batch, hipStream_t st) {
+// NW: 8 waves per workgroup when there are enough column groups to fill the chip, 16 when there are
+// few (each workgroup then has to keep twice as many bytes in flight).
+template <int WB, int B, int MP, int NW>
+mx_status launch_dot_nw(const DotArgs& a, int64_t batch, hipStream_t st) {
     const size_t smem = ((size_t)MP * a.g.chunks * 4 * 2 * (B / 8) + (size_t)MP * a.g.chunks) * 4 +
-                        (size_t)kDotWaves * MP * 32 * 4;
+                        (size_t)NW * MP * 32 * 4;
     if (smem > 160 * 1024) return MX_ERR_UNSUPPORTED;
-    auto kern = gemv_dot_kernel<WB, B, MP, kDotWaves, kDotDepth>;
+    auto kern = gemv_dot_kernel<WB, B, MP, NW, kDotDepth>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
@@ -215,9 +268,15 @@ mx_status launch_dot(const DotArgs& a, int64_t batch, hipStream_t st) {
         configured = true;
     }
     dim3 grid((unsigned)a.g.groupsB, (unsigned)batch);
-    hipLaunchKernelGGL(kern, grid, dim3(kDotWaves * 64), smem, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, a);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
+}
+
+template <int WB, int B, int MP>
+mx_status launch_dot(const DotArgs& a, int64_t batch, hipStream_t st) {
+    if (a.g.groupsB * batch < 256) return launch_dot_nw<WB, B, MP, 16>(a, batch, st);
+    return launch_dot_nw<WB, B, MP, 8>(a, batch, st);
 }
 
 template <int B, int MP>
@@ -244,10 +303,20 @@ mx_status dispatch_m(const DotArgs& a, int wb, int64_t batch, hipStream_t st) {
 }  // namespace
 
 // M <= 4.  MX_ERR_UNSUPPORTED when the activations do not fit in LDS (the caller falls back).
-mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, hipStream_t st) {
+// x != null: fused form, the left operand is quantized from fp32 (format fx) inside the kernel.
+mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, hipStream_t st, const float* x,
+                   int64_t x_stride, const mx_format* fx) {
     DotArgs a;
     a.g = g;
     a.wa = wa;
+    a.x = x;
+    a.x_stride = x_stride;
+    a.bias = a.emax = a.rounding = 0;
+    if (x != nullptr) {
+        a.bias = (1 << (fx->exp_bits - 1)) - 1;
+        a.emax = ((1 << fx->exp_bits) - 1) - a.bias;
+        a.rounding = fx->rounding;
+    }
     if (g.chunks <= 0) return MX_ERR_UNSUPPORTED;
     switch (block) {
         case 16: return dispatch_m<16>(a, wb, batch, st);

@@ -2,7 +2,7 @@
 // straight into the fragment layout, then the decode kernel of mx_gemm streams the packed weights.
 // The quantizer arithmetic is the one of mx_quantize (Section 4.1 format; Section 3.2 emulation
 // semantics: quantize the input, then the operator).
-#include "mx_common.h"
+#include "mx_gemm.h"
 
 namespace mx {
 namespace {
@@ -141,6 +141,13 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
     if (K > 0 && (!x || !A_scratch || !B_packed)) return MX_ERR_BAD_ARG;
     if (((uintptr_t)x & 3) || ((uintptr_t)A_scratch & 255)) return MX_ERR_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
+    if (K > 0 && M <= 2) {
+        // one launch: the dot-product decode kernel quantizes the activations on its way into LDS
+        // (same arithmetic, same accumulation order as the two-launch form); A_scratch is not touched
+        const GemmArgs g = fragment_args(M, N, K, A_scratch, fx, B_packed, fb, Y, ldy, M * ldy);
+        const mx_status s = gemv_dot(g, fx.mant_bits, fb.mant_bits, fx.block, 1, st, x, row_stride, &fx);
+        if (s != MX_ERR_UNSUPPORTED) return s;
+    }
     if (K > 0) {
         // rows M..31 of the row group stay as they are: the decode kernel does not read them
         mx_status s = run_lq(x, 1, M, M, K, row_stride, 0, fx, (uint8_t*)A_scratch, st);
