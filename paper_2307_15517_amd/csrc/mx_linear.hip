@@ -11,72 +11,133 @@ struct LinQuantArgs {
     const float* x;
     uint8_t* packed;
     int64_t M;           // rows holding data
-    int64_t rows_out;    // rows written: M (decode: the rest of the row group is never read) or M padded to 32
+    int64_t rows_out;    // rows covered by the launch; whole row groups of 32 are written
     int64_t K, row_stride, batch_stride, chunks, matrix_bytes;
     int32_t piece, record, bias, emax;
+    int32_t vec;         // x and its strides allow 16-byte loads
 };
 
-// One thread per (row m < rows_out, block slot b < 4*chunks); grid.y = batch.  Slots past K and
-// rows past M hold zero mantissas and exponent byte 0.
+// One wave per record of the fragment layout (32 rows x 4 blocks); four waves, i.e. four consecutive
+// chunks, per workgroup; grid.y = batch.  A record is built in passes of 64 columns: the wave reads
+// 32 rows x 256 bytes as whole row segments (four rows per load instruction) and turns them through
+// its own LDS tile, after which lane 32*h + i holds half h of every block of row i that the pass
+// covers; the block maximum is completed with the partner lane.  The finished pieces and exponent
+// bytes go back through the same LDS tile, so that the record leaves as one contiguous run of
+// 16-byte stores.  Slots past K and rows in [M, 32*groups) hold zero mantissas and exponent byte 0.
+constexpr int kLqRowPitch = 256 + 16;     // bytes; the 16-byte skew spreads the lanes' rows over the banks
+constexpr int kLqTile = 32 * kLqRowPitch; // also holds the largest record (64 * 128 + 128 bytes)
+
 template <int W, int B, int RND>
 __global__ __launch_bounds__(256) void quantize_to_fragments_kernel(LinQuantArgs a) {
-    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t slots = a.chunks * 4;
-    if (t >= a.rows_out * slots) return;
-    const int64_t m = t / slots, b = t - m * slots;
-    const int64_t c = b >> 2;
-    const int j = (int)(b & 3);
-    const bool inside = b * B < a.K && m < a.M;
-    const float* xrow = a.x + blockIdx.y * a.batch_stride + m * a.row_stride;
-    float v[B];
-    uint32_t am = 0;
-#pragma unroll
-    for (int k = 0; k < B; ++k) {
-        v[k] = inside ? xrow[b * B + k] : 0.f;
-        uint32_t ab = __float_as_uint(v[k]) & 0x7fffffffu;
-        am = ab > am ? ab : am;
-    }
-    const int ef = (int)(am >> 23);
-    int E = ef == 0 ? -127 : ef - 127;
-    E = E < -a.bias ? -a.bias : E;
-    E = E > a.emax ? a.emax : E;
-    const int shift = (W - 2) - E;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * kLqTile];
+    constexpr int kPieceDw = B * W / 16;          // dwords of one lane piece: four half blocks
+    constexpr int kPasses = 4 * B / 64;           // 64 columns per pass
+    constexpr int kBlocksPerPass = 64 / B > 0 ? 64 / B : 1;
+    constexpr int kHalf = B / 2;
+    constexpr int kPerPass = B >= 64 ? 32 : kBlocksPerPass * kHalf;   // elements of a lane per pass (always 32)
+    static_assert(kPerPass == 32, "a lane quantizes 32 elements per pass");
     constexpr float qmax = (float)((1 << (W - 1)) - 1);
-    uint8_t* rec = a.packed + blockIdx.y * a.matrix_bytes + ((m >> 5) * a.chunks + c) * a.record;
-    const int i = (int)(m & 31);
-    constexpr int kHalfBytes = B * W / 16;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    uint8_t* lds = lds_all + wv * kLqTile;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t cq = (a.chunks + 3) / 4;
+    const int64_t grp = blockIdx.x / cq, c = (blockIdx.x - grp * cq) * 4 + wv;
+    if (c >= a.chunks) return;                    // whole wave; no workgroup barrier below
+    const float* xb = a.x + blockIdx.y * a.batch_stride;
+
+    uint32_t piece[kPieceDw];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        // (B/2)*W bits of half h, as bytes
-        uint8_t out[kHalfBytes];
+    for (int d = 0; d < kPieceDw; ++d) piece[d] = 0;
+    uint32_t exps = 0;
 #pragma unroll
-        for (int d = 0; d < kHalfBytes; ++d) out[d] = 0;
+    for (int p = 0; p < kPasses; ++p) {
+        float4 in[8];
+        const int64_t col = c * (4 * B) + p * 64 + (lane & 15) * 4;
 #pragma unroll
-        for (int k = 0; k < B / 2; ++k) {
-            float s = __builtin_ldexpf(v[h * (B / 2) + k], shift);
-            float r = RND == MX_RNE ? __builtin_rintf(s) : __builtin_truncf(s);
-            r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
-            const uint32_t code = (uint32_t)(int)r & ((1u << W) - 1u);
-            int pos = k;                                   // element position inside the half block
-            if (W == 4) {                                  // nibble order e0 e4 e1 e5 e2 e6 e3 e7 per 8
-                const int t8 = k & 7;
-                pos = (k & ~7) + (t8 < 4 ? 2 * t8 : 2 * (t8 - 4) + 1);
+        for (int r = 0; r < 8; ++r) {
+            const int64_t row = grp * 32 + 4 * r + (lane >> 4);
+            in[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < a.M && col < a.K) {
+                const float* src = xb + row * a.row_stride + col;
+                if (a.vec) in[r] = *reinterpret_cast<const float4*>(src);
+                else in[r] = make_float4(src[0], src[1], src[2], src[3]);
             }
-            const int bit = pos * W;
-            out[bit >> 3] |= (uint8_t)(code << (bit & 7));
-            if ((bit & 7) + W > 8) out[(bit >> 3) + 1] |= (uint8_t)(code >> (8 - (bit & 7)));
         }
-        uint8_t* dst = rec + (int64_t)(32 * h + i) * a.piece + j * kHalfBytes;
+        if (p > 0) __builtin_amdgcn_wave_barrier();          // the previous pass has read its tile
 #pragma unroll
-        for (int d = 0; d < kHalfBytes; ++d) dst[d] = out[d];
+        for (int r = 0; r < 8; ++r)
+            *reinterpret_cast<float4*>(lds + (4 * r + (lane >> 4)) * kLqRowPitch + (lane & 15) * 16) = in[r];
+        __builtin_amdgcn_wave_barrier();
+
+        // the lane's 32 elements of this pass: B/2 consecutive floats of each of its 64/B blocks
+        float v[32];
+#pragma unroll
+        for (int jj = 0; jj < kBlocksPerPass; ++jj) {
+            constexpr int kRun = B >= 64 ? 32 : kHalf;       // consecutive floats per block
+            const uint8_t* src = lds + i * kLqRowPitch + (jj * (B >= 64 ? 64 : B) + h * kRun) * 4;
+#pragma unroll
+            for (int q4 = 0; q4 < kRun / 4; ++q4) {
+                const float4 t = *reinterpret_cast<const float4*>(src + q4 * 16);
+                v[jj * kRun + 4 * q4] = t.x; v[jj * kRun + 4 * q4 + 1] = t.y;
+                v[jj * kRun + 4 * q4 + 2] = t.z; v[jj * kRun + 4 * q4 + 3] = t.w;
+            }
+        }
+        const bool row_in = grp * 32 + i < a.M;
+#pragma unroll
+        for (int jj = 0; jj < kBlocksPerPass; ++jj) {
+            constexpr int kRun = B >= 64 ? 32 : kHalf;
+            const int j = p * kBlocksPerPass + jj;           // block slot inside the chunk (compile time)
+            uint32_t am = 0;
+#pragma unroll
+            for (int k = 0; k < kRun; ++k) {
+                const uint32_t ab = __float_as_uint(v[jj * kRun + k]) & 0x7fffffffu;
+                am = ab > am ? ab : am;
+            }
+            const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
+            am = o > am ? o : am;
+            const int ef = (int)(am >> 23);
+            int E = ef == 0 ? -127 : ef - 127;
+            E = E < -a.bias ? -a.bias : E;
+            E = E > a.emax ? a.emax : E;
+            const int shift = (W - 2) - E;
+            const bool inside = row_in && (c * 4 + j) * B < a.K;
+            exps |= (inside ? (uint32_t)(E + a.bias) : 0u) << (8 * j);
+#pragma unroll
+            for (int k = 0; k < kRun; ++k) {
+                const float s = __builtin_ldexpf(v[jj * kRun + k], shift);
+                float r = RND == MX_RNE ? __builtin_rintf(s) : __builtin_truncf(s);
+                r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+                const uint32_t code = (uint32_t)(int)r & ((1u << W) - 1u);
+                int pos = k;                                   // element position inside the half block
+                if (W == 4) {                                  // nibble order e0 e4 e1 e5 e2 e6 e3 e7 per 8
+                    const int t8 = k & 7;
+                    pos = (k & ~7) + (t8 < 4 ? 2 * t8 : 2 * (t8 - 4) + 1);
+                }
+                const int bit = (j * kHalf + pos) * W;         // compile time after unrolling
+                piece[bit >> 5] |= code << (bit & 31);
+                if ((bit & 31) + W > 32) piece[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+            }
+        }
     }
-    rec[64 * a.piece + i * 4 + j] = inside ? (uint8_t)(E + a.bias) : (uint8_t)0;
+    // record image in LDS: 64 pieces, then the 32 exponent dwords
+    __builtin_amdgcn_wave_barrier();
+    uint32_t* img = reinterpret_cast<uint32_t*>(lds);
+#pragma unroll
+    for (int d = 0; d < kPieceDw; ++d) img[lane * kPieceDw + d] = piece[d];
+    if (h == 0) img[64 * kPieceDw + i] = exps;
+    __builtin_amdgcn_wave_barrier();
+    constexpr int kRec16 = (64 * kPieceDw * 4 + 128) / 16;
+    uint4* dst = reinterpret_cast<uint4*>(a.packed + blockIdx.y * a.matrix_bytes + (grp * a.chunks + c) * a.record);
+#pragma unroll
+    for (int it = 0; it < (kRec16 + 63) / 64; ++it) {
+        const int idx = it * 64 + lane;
+        if (idx < kRec16) dst[idx] = reinterpret_cast<const uint4*>(lds)[idx];
+    }
 }
 
 template <int W, int B>
 mx_status launch_lq(const LinQuantArgs& a, int64_t batch, int rnd, hipStream_t st) {
-    const int64_t threads = a.rows_out * a.chunks * 4;
-    dim3 grid((unsigned)ceil_div(threads, 256), (unsigned)batch);
+    dim3 grid((unsigned)(ceil_div(a.rows_out, 32) * ceil_div(a.chunks, 4)), (unsigned)batch);
     if (rnd == MX_RNE)
         hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RNE>), grid, dim3(256), 0, st, a);
     else
@@ -107,7 +168,8 @@ mx_status run_lq(const float* x, int64_t batch, int64_t M, int64_t rows_out, int
     a.piece = ga.piece; a.record = ga.record;
     a.bias = (1 << (f.exp_bits - 1)) - 1;
     a.emax = ((1 << f.exp_bits) - 1) - a.bias;
-    if (ceil_div(rows_out * ga.chunks * 4, 256) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+    a.vec = (((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0 && (batch_stride & 3) == 0) ? 1 : 0;
+    if (ceil_div(rows_out, 32) * ceil_div(ga.chunks, 4) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     switch (f.block) {
         case 16: MX_SW(f.mant_bits, kW, return (launch_lq<kW, 16>(a, batch, f.rounding, st))); break;
         case 32: MX_SW(f.mant_bits, kW, return (launch_lq<kW, 32>(a, batch, f.rounding, st))); break;
@@ -149,7 +211,6 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
         if (s != MX_ERR_UNSUPPORTED) return s;
     }
     if (K > 0) {
-        // rows M..31 of the row group stay as they are: the decode kernel does not read them
         mx_status s = run_lq(x, 1, M, M, K, row_stride, 0, fx, (uint8_t*)A_scratch, st);
         if (s != MX_OK) return s;
     }

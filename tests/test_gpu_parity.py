@@ -362,6 +362,46 @@ def test_gemm_is_deterministic():
     assert torch.equal(y1, y2)
 
 
+@pytest.mark.parametrize("seed", [0, 3])
+def test_attention_shaped_products_mixed_widths(seed):
+    """Reduced form of the mixed-precision attention workload: per head Q K^T (blocks of 16 along the head
+    dimension) and P V (blocks of 16 along the sequence: V is quantized along its strided axis), every
+    tensor with its own width drawn by seed, batched over the heads."""
+    heads, seq, dim, block = 4, 256, 128, 16
+    wq, wk, wp, wv = inputs.attention_widths(seed)
+    Q, K, V = inputs.attention_qkv(seed, heads, seq, dim)
+    say("attention widths", wq, wk, wp, wv)
+    fq, fk, fp_, fv = (mx.fmt(block, w) for w in (wq, wk, wp, wv))
+    # scores = Q K^T
+    qm, qe = mx.quantize(dev(Q), fq)
+    km, ke = mx.quantize(dev(K), fk)
+    A = mx.pack(qm, qe, heads, seq, dim, fq)
+    B = mx.pack(km, ke, heads, seq, dim, fk)
+    S = mx.gemm(A, fq, B, fk, seq, seq, dim, batch=heads)
+    torch.cuda.synchronize()
+    P = torch.softmax(S / np.sqrt(dim), dim=-1).contiguous()          # fp32, outside the MXInt path
+    # out = P V: P blocked along its rows' sequence axis, V along the sequence (its strided axis)
+    pm, pe = mx.quantize(P, fp_)
+    vm, ve = mx.quantize(dev(V), fv, axis=0)                          # canonical form of V^T: [heads, dim, seq]
+    A2 = mx.pack(pm, pe, heads, seq, seq, fp_)
+    B2 = mx.pack(vm, ve, heads, dim, seq, fv)
+    O = mx.gemm(A2, fp_, B2, fv, seq, dim, seq, batch=heads)
+    torch.cuda.synchronize()
+    Ph = host(P)
+    for hd in range(heads):
+        oq, oqe = orc.quantize(Q[hd], block, wq)
+        ok, oke = orc.quantize(K[hd], block, wk)
+        s_ref, s_mag = orc.gemm(oq, oqe, wq, ok, oke, wk, block, want_mag=True)
+        check_product(host(S)[hd], s_ref, s_mag, "scores head %d" % hd)
+        op, ope = orc.quantize(Ph[hd], block, wp)
+        ov, ove = orc.quantize(V[hd], block, wv, axis=0)
+        assert np.array_equal(host(pm).reshape(heads, -1)[hd], orc.pack_bits(op, wp).reshape(-1))
+        assert np.array_equal(host(vm).reshape(heads, -1)[hd], orc.pack_bits(ov, wv).reshape(-1))
+        assert np.array_equal(host(ve).reshape(heads, -1)[hd], ove.reshape(-1))
+        o_ref, o_mag = orc.gemm(op, ope, wp, ov, ove, wv, block, want_mag=True)
+        check_product(host(O)[hd], o_ref, o_mag, "output head %d" % hd)
+
+
 # ----------------------------------------------------------------------------------------------
 # The block-scaled matrix-core layout (block 32 / 64) and the product kernel that reads it
 # ----------------------------------------------------------------------------------------------
