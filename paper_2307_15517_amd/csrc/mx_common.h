@@ -65,4 +65,34 @@ __device__ __forceinline__ int stream_get(const uint32_t* s, int bit) {
     return ((int)(v << (32 - W))) >> (32 - W);
 }
 
+// Buffer loads: a lane whose byte offset lies at or beyond `bytes` gets zeros and touches no memory,
+// so a load past the end needs no branch around it -- the number of loads a wave has in flight is
+// then the same on every path, and the waits the compiler places stay exact (a load inside a
+// conditional makes every later wait a wait for all outstanding loads).
+using BufRsrc = __amdgpu_buffer_rsrc_t;
+__device__ __forceinline__ BufRsrc make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+template <int NDW>
+__device__ __forceinline__ void buf_load_dwords(BufRsrc r, uint32_t off, uint32_t* out) {
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+    if constexpr (NDW % 4 == 0) {
+#pragma unroll
+        for (int d = 0; d < NDW / 4; ++d) {
+            const u4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off + 16 * d, 0, 0);
+            out[4 * d] = v.x; out[4 * d + 1] = v.y; out[4 * d + 2] = v.z; out[4 * d + 3] = v.w;
+        }
+    } else if constexpr (NDW % 2 == 0) {
+#pragma unroll
+        for (int d = 0; d < NDW / 2; ++d) {
+            const u2 v = __builtin_amdgcn_raw_buffer_load_b64(r, off + 8 * d, 0, 0);
+            out[2 * d] = v.x; out[2 * d + 1] = v.y;
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < NDW; ++d) out[d] = __builtin_amdgcn_raw_buffer_load_b32(r, off + 4 * d, 0, 0);
+    }
+}
+
 }  // namespace mx

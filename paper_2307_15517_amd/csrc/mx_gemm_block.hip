@@ -264,7 +264,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
     constexpr int XD = 16 * kDwA + 8;            // dwords kept per chunk: 16 lane pieces (rows 0..7, both halves) + 8 rows of exponents
     extern __shared__ __attribute__((aligned(16))) uint32_t xs[];
     float* red = reinterpret_cast<float*>(xs + g.chunks * XD);          // [NW][MR][64]
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 31, h = lane >> 5;
     const int64_t gb = blockIdx.x;
     const int64_t bz = blockIdx.y;
@@ -273,27 +273,26 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
     const int eadj = g.eadj - Unpack<WA, B>::kScaleLog2 - Unpack<WB, B>::kScaleLog2;
     const int chunks = (int)g.chunks;
 
-    // ring of D chunks of weights per wave; chunk number t of this wave is chunk wave + t*NW
+    // ring of D chunks of weights per wave; chunk number t of this wave is chunk wave + t*NW, and a
+    // chunk number past the end of the column group reads zeros (no branch around a load: the waits
+    // the compiler places then count exactly the loads that are in flight)
+    const BufRsrc rB = make_rsrc(Bbase, (uint32_t)(chunks * g.recordB));
     uint32_t pb[D][kDwB], eb[D];
     auto fetch = [&](int slot, int t) {
-        const int c = wave + t * NW;
-        if (c < chunks) {
-            const uint8_t* recB = Bbase + (int64_t)c * g.recordB;
-            load_dwords<kDwB>(recB + lane * (kDwB * 4), pb[slot]);
-            eb[slot] = reinterpret_cast<const uint32_t*>(recB + 64 * (kDwB * 4))[i];
-        }
+        const uint32_t off = (uint32_t)(wave + t * NW) * (uint32_t)g.recordB;
+        buf_load_dwords<kDwB>(rB, off + lane * (kDwB * 4), pb[slot]);
+        buf_load_dwords<1>(rB, off + 64 * (kDwB * 4) + i * 4, &eb[slot]);
     };
-#pragma unroll
-    for (int u = 0; u < D; ++u) fetch(u, u);
 
-    // left operand -> LDS (rows 0..7 of row group 0), in units of UD dwords, several loads in flight
+    // left operand -> LDS (rows 0..7 of row group 0), in units of UD dwords, several loads in flight.
+    // Loads return in the order of issue: the first batch of the left operand is requested before the
+    // ring of weights, so that it does not wait behind them.
     {
         constexpr int UD = (kDwA % 4 == 0) ? 4 : 1;          // dwords per unit
         constexpr int UPC = XD / UD;                         // units per chunk (XD = 16*kDwA + 8)
         constexpr int UNROLL = 4;
         const int total = chunks * UPC;
-        for (int base = threadIdx.x; base < total; base += NW * 64 * UNROLL) {
-            uint32_t v[UNROLL][UD];
+        auto batch_load = [&](int base, uint32_t (*v)[UD]) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const int idx = base + u * NW * 64;
@@ -310,6 +309,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
                     load_dwords<UD>(src, v[u]);
                 }
             }
+        };
+        auto batch_store = [&](int base, uint32_t (*v)[UD]) {
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const int idx = base + u * NW * 64;
@@ -318,6 +319,15 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
                     for (int d = 0; d < UD; ++d) xs[idx * UD + d] = v[u][d];
                 }
             }
+        };
+        uint32_t v[UNROLL][UD];
+        batch_load(threadIdx.x, v);
+#pragma unroll
+        for (int u = 0; u < D; ++u) fetch(u, u);
+        batch_store(threadIdx.x, v);
+        for (int base = threadIdx.x + NW * 64 * UNROLL; base < total; base += NW * 64 * UNROLL) {
+            batch_load(base, v);
+            batch_store(base, v);
         }
     }
     __syncthreads();
@@ -325,13 +335,22 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
     float acc[MR];
 #pragma unroll
     for (int r = 0; r < MR; ++r) acc[r] = 0.f;
-    const int per_wave = (chunks - wave + NW - 1) / NW;          // chunks of this wave (chunks >= NW is not required)
+    const int per_wave = (chunks - wave + NW - 1) / NW;          // chunks of this wave, wave-uniform (chunks >= NW is not required)
     for (int t0 = 0; t0 < per_wave; t0 += D) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             const int t = t0 + u;
-            if (t < per_wave) {
-                const int c = wave + t * NW;
+            const bool live = t < per_wave;                       // scalar condition: no load depends on it
+            const int c = wave + t * NW;
+            uint32_t fbv[4][kHalfDw];
+            uint32_t ebv = 0;
+            if (live) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) Unpack<WB, B>::run(pb[u], j, fbv[j]);
+                ebv = eb[u];
+            }
+            fetch(u, t + D);                                      // the slot is free: refill it
+            if (live) {
                 const uint32_t* xc = xs + c * XD;
                 uint32_t pa[kDwA], ea[4];
                 if (i < 8) {
@@ -343,11 +362,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) ea[r] = xc[16 * kDwA + 4 * h + r];
-                uint32_t fbv[4][kHalfDw];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) Unpack<WB, B>::run(pb[u], j, fbv[j]);
-                const uint32_t ebv = eb[u];
-                fetch(u, t + D);                              // the slot is free: refill it
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     uint32_t fa[kHalfDw];
@@ -402,7 +416,7 @@ mx_status launch(const GemmArgs& g, int64_t batch, hipStream_t st) {
         constexpr int XD = 16 * Piece<WA, B>::kDw + 8;
         const int nw = g.groupsB * batch < 256 ? 16 : 8;
         const size_t smem = (size_t)g.chunks * XD * 4 + (size_t)nw * 4 * 64 * 4;
-        if (g.chunks > 0 && g.chunks < (1 << 20) && smem <= 160 * 1024) {
+        if (g.chunks > 0 && (g.chunks + 1024) * g.recordB < (1LL << 31) && smem <= 160 * 1024) {
             if (nw == 16) {
                 if (g.M == 1) return launch_stream<WA, WB, B, 1, 16>(g, batch, smem, st);
                 return launch_stream<WA, WB, B, 4, 16>(g, batch, smem, st);

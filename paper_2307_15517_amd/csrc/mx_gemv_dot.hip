@@ -85,6 +85,7 @@ struct DotArgs {
     // fused form (mx_linear): the left operand is still fp32 and is quantized on the way into LDS
     const float* x;      // null: take the packed left operand g.A
     int64_t x_stride;
+    int32_t x_vec;       // x and its stride allow 16-byte loads
     int32_t bias, emax, rounding;
 };
 
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
     uint32_t* x8 = lds;
     uint32_t* xe = x8 + MP * chunks * 4 * 2 * kHalfDw;
     float* red = reinterpret_cast<float*>(xe + MP * chunks);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int i = lane & 31, h = lane >> 5;
     const int64_t gb = blockIdx.x;
     const int64_t bz = blockIdx.y;
@@ -110,63 +111,86 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
     const int eadj = g.eadj - UnpackB<WB, B>::kScaleLog2;
     const int pieceA = B * a.wa / 4;             // bytes of a left-operand lane piece
 
+    // ring of D chunks of this column group's records; a chunk number past the end reads zeros
+    const BufRsrc rB = make_rsrc(Bbase, (uint32_t)(chunks * g.recordB));
     uint32_t pb[D][kDwB], eb[D];
     auto fetch = [&](int slot, int t) {
-        const int c = wave + t * NW;
-        if (c < chunks) {
-            const uint8_t* recB = Bbase + (int64_t)c * g.recordB;
-            load_dwords<kDwB>(recB + lane * (kDwB * 4), pb[slot]);
-            eb[slot] = reinterpret_cast<const uint32_t*>(recB + 64 * (kDwB * 4))[i];
-        }
+        const uint32_t off = (uint32_t)(wave + t * NW) * (uint32_t)g.recordB;
+        buf_load_dwords<kDwB>(rB, off + lane * (kDwB * 4), pb[slot]);
+        buf_load_dwords<1>(rB, off + 64 * (kDwB * 4) + i * 4, &eb[slot]);
     };
-#pragma unroll
-    for (int u = 0; u < D; ++u) fetch(u, u);
-
+    // Loads return in the order of issue, so whatever the workgroup needs first is requested first:
+    // the activations, then the ring of weights; the arithmetic on the activations then runs while
+    // the weights are in flight.
     if (a.x != nullptr) {
-        // fp32 activations -> MXInt (the arithmetic of mx_quantize) -> int8 in LDS: one item per (row, block)
-        const int nblk = (int)(g.K / B);
+        // fp32 activations -> MXInt (the arithmetic of mx_quantize) -> int8 in LDS.  One item is four
+        // consecutive elements of a row, items of consecutive lanes are consecutive (a wave reads 1 KB
+        // per instruction), so a block is B/4 consecutive lanes and its maximum takes log2(B/4) DPP
+        // steps.  Every workgroup reads the same activations; each starts at a different sweep so that
+        // they do not all ask the same cache channel at the same time.
+        constexpr int T = NW * 64;
+        constexpr int XU = 8;                                   // items per thread requested before the weights
+        const int kpad = chunks * 4 * B;                        // row length in LDS (slots past K hold zeros)
+        const int sweeps = (kpad / 4 + T - 1) / T;
+        const int n_it = MP * sweeps;
+        const int rot = (int)(gb % sweeps);
         const float qmax = (float)((1 << (a.wa - 1)) - 1);
-        for (int idx = threadIdx.x; idx < MP * chunks * 4; idx += NW * 64) {
-            const int blk = idx % (chunks * 4), m = idx / (chunks * 4);
-            uint32_t* dst = x8 + (m * chunks * 4 + blk) * 2 * kHalfDw;
-            uint32_t out[2 * kHalfDw];
-            int ebyte = 0;
-            if (m < g.M && blk < nblk) {
-                float v[B];
-                const float* src = a.x + (int64_t)m * a.x_stride + (int64_t)blk * B;
-                uint32_t am = 0;
-#pragma unroll
-                for (int k = 0; k < B; ++k) {
-                    v[k] = src[k];
-                    const uint32_t ab = __float_as_uint(v[k]) & 0x7fffffffu;
-                    am = ab > am ? ab : am;
-                }
-                const int ef = (int)(am >> 23);
-                int E = ef == 0 ? -127 : ef - 127;
-                E = E < -a.bias ? -a.bias : E;
-                E = E > a.emax ? a.emax : E;
-                const int shift = (a.wa - 2) - E;
-#pragma unroll
-                for (int d = 0; d < 2 * kHalfDw; ++d) {
-                    uint32_t o = 0;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const float sc = __builtin_ldexpf(v[4 * d + t], shift);
-                        float r = a.rounding == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
-                        r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
-                        o |= ((uint32_t)(int)r & 0xFFu) << (8 * t);
-                    }
-                    out[d] = o;
-                }
-                ebyte = E + a.bias;
-            } else {
-#pragma unroll
-                for (int d = 0; d < 2 * kHalfDw; ++d) out[d] = 0;
+        uint8_t* xeb = reinterpret_cast<uint8_t*>(xe);
+        auto item_pos = [&](int it, int& m, int& e) {
+            m = it / sweeps;
+            int kk = it - m * sweeps + rot;
+            kk = kk >= sweeps ? kk - sweeps : kk;
+            e = 4 * ((int)threadIdx.x + T * kk);
+        };
+        auto item_load = [&](int it) -> float4 {
+            int m, e;
+            item_pos(it, m, e);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m < g.M && e < g.K) {                           // K is a multiple of 4: all four or none
+                const float* src = a.x + (int64_t)m * a.x_stride + e;
+                if (a.x_vec) v = *reinterpret_cast<const float4*>(src);
+                else v = make_float4(src[0], src[1], src[2], src[3]);
             }
+            return v;
+        };
+        auto item_store = [&](int it, const float4& v) {
+            int m, e;
+            item_pos(it, m, e);
+            const uint32_t b0 = __float_as_uint(v.x) & 0x7fffffffu, b1 = __float_as_uint(v.y) & 0x7fffffffu;
+            const uint32_t b2 = __float_as_uint(v.z) & 0x7fffffffu, b3 = __float_as_uint(v.w) & 0x7fffffffu;
+            uint32_t am = b0 > b1 ? b0 : b1, a2 = b2 > b3 ? b2 : b3;
+            am = am > a2 ? am : a2;
+            uint32_t o;
+            o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);  am = o > am ? o : am;   // lane ^ 1
+            o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0x4E, 0xF, 0xF, true);  am = o > am ? o : am;   // lane ^ 2
+            if (B >= 32) { o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0x141, 0xF, 0xF, true); am = o > am ? o : am; }   // 7 - lane within 8
+            if (B >= 64) { o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0x140, 0xF, 0xF, true); am = o > am ? o : am; }   // 15 - lane within 16
+            const int ef = (int)(am >> 23);
+            int E = ef == 0 ? -127 : ef - 127;
+            E = E < -a.bias ? -a.bias : E;
+            E = E > a.emax ? a.emax : E;
+            const int shift = (a.wa - 2) - E;
+            auto code = [&](float x) -> uint32_t {
+                const float sc = __builtin_ldexpf(x, shift);
+                float r = a.rounding == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
+                r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+                return (uint32_t)(int)r & 0xFFu;
+            };
+            if (e < kpad) {
+                x8[(m * kpad + e) >> 2] = code(v.x) | (code(v.y) << 8) | (code(v.z) << 16) | (code(v.w) << 24);
+                if ((e & (B - 1)) == 0) xeb[m * chunks * 4 + e / B] = (m < g.M && e < g.K) ? (uint8_t)(E + a.bias) : (uint8_t)0;
+            }
+        };
+        float4 xv[XU];
 #pragma unroll
-            for (int d = 0; d < 2 * kHalfDw; ++d) dst[d] = out[d];
-            reinterpret_cast<uint8_t*>(xe)[(m * chunks + (blk >> 2)) * 4 + (blk & 3)] = (uint8_t)ebyte;
-        }
+        for (int it = 0; it < XU; ++it)
+            if (it < n_it) xv[it] = item_load(it);
+#pragma unroll
+        for (int u = 0; u < D; ++u) fetch(u, u);
+#pragma unroll
+        for (int it = 0; it < XU; ++it)
+            if (it < n_it) item_store(it, xv[it]);
+        for (int it = XU; it < n_it; ++it) item_store(it, item_load(it));
     } else {
     // packed activations -> int8 in LDS: one item per (row, chunk, half)
     for (int idx = threadIdx.x; idx < MP * chunks * 2; idx += NW * 64) {
@@ -197,24 +221,30 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
             if (hh == 0) xe[m * chunks + c] = 0;
         }
     }
+#pragma unroll
+    for (int u = 0; u < D; ++u) fetch(u, u);
     }
     __syncthreads();
 
     float acc[MP];
 #pragma unroll
     for (int m = 0; m < MP; ++m) acc[m] = 0.f;
-    const int per_wave = (chunks - wave + NW - 1) / NW;
+    const int per_wave = (chunks - wave + NW - 1) / NW;          // wave-uniform
     for (int t0 = 0; t0 < per_wave; t0 += D) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             const int t = t0 + u;
-            if (t < per_wave) {
-                const int c = wave + t * NW;
-                uint32_t fb[4][kHalfDw];
+            const bool live = t < per_wave;                       // scalar condition: no load depends on it
+            const int c = wave + t * NW;
+            uint32_t fb[4][kHalfDw];
+            uint32_t ebv = 0;
+            if (live) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) UnpackB<WB, B>::run(pb[u], j, fb[j]);
-                const uint32_t ebv = eb[u];
-                fetch(u, t + D);                                  // the slot is free: refill it
+                ebv = eb[u];
+            }
+            fetch(u, t + D);                                      // the slot is free: refill it
+            if (live) {
                 uint32_t exm[MP];
 #pragma unroll
                 for (int m = 0; m < MP; ++m) exm[m] = xe[m * chunks + c];
@@ -251,7 +281,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
     }
 }
 
-constexpr int kDotDepth = 8;
+constexpr int kDotDepth = 5;
 
 // NW: 8 waves per workgroup when there are enough column groups to fill the chip, 16 when there are
 // few (each workgroup then has to keep twice as many bytes in flight).
@@ -311,6 +341,7 @@ mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, 
     a.wa = wa;
     a.x = x;
     a.x_stride = x_stride;
+    a.x_vec = (x != nullptr && ((uintptr_t)x & 15) == 0 && (x_stride & 3) == 0) ? 1 : 0;
     a.bias = a.emax = a.rounding = 0;
     if (x != nullptr) {
         a.bias = (1 << (fx->exp_bits - 1)) - 1;
@@ -318,6 +349,7 @@ mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, 
         a.rounding = fx->rounding;
     }
     if (g.chunks <= 0) return MX_ERR_UNSUPPORTED;
+    if ((g.chunks + 1024) * g.recordB >= (1LL << 31)) return MX_ERR_UNSUPPORTED;   // 32-bit ring offsets
     switch (block) {
         case 16: return dispatch_m<16>(a, wb, batch, st);
         case 32: return dispatch_m<32>(a, wb, batch, st);

@@ -402,6 +402,34 @@ def test_attention_shaped_products_mixed_widths(seed):
         check_product(host(O)[hd], o_ref, o_mag, "output head %d" % hd)
 
 
+def test_attention_full_size_sampled_heads_and_rows():
+    """The attention workload at its full size (32 heads, 2048 positions, head dimension 128) through the
+    fused quantize+pack path the benchmark times; the oracle computes two heads on a 32-row window."""
+    heads, seq, dim, block, seed = 32, 2048, 128, 16, 0
+    wq, wk, wp, wv = inputs.attention_widths(seed)
+    Q, K, V = inputs.attention_qkv(seed, heads, seq, dim)
+    fq, fk, fp_, fv = (mx.fmt(block, w) for w in (wq, wk, wp, wv))
+    A = mx.quantize_pack(dev(Q), fq)
+    B = mx.quantize_pack(dev(K), fk)
+    S = mx.gemm(A, fq, B, fk, seq, seq, dim, batch=heads)
+    P = torch.softmax(S / np.sqrt(dim), dim=-1).contiguous()
+    A2 = mx.quantize_pack(P, fp_)
+    vm, ve = mx.quantize(dev(V), fv, axis=0)
+    B2 = mx.pack(vm, ve, heads, dim, seq, fv)
+    O = mx.gemm(A2, fp_, B2, fv, seq, dim, seq, batch=heads)
+    torch.cuda.synchronize()
+    r0, r1 = 1500, 1532
+    for hd in (0, 31):
+        oq, oqe = orc.quantize(Q[hd], block, wq)
+        ok, oke = orc.quantize(K[hd], block, wk)
+        s_ref, s_mag = orc.gemm(oq, oqe, wq, ok, oke, wk, block, rows=(r0, r1), want_mag=True)
+        say("scores head", hd, "worst", check_product(host(S[hd, r0:r1]), s_ref[r0:r1], s_mag[r0:r1], "scores"))
+        op, ope = orc.quantize(host(P[hd]), block, wp)
+        ov, ove = orc.quantize(V[hd], block, wv, axis=0)
+        o_ref, o_mag = orc.gemm(op, ope, wp, ov, ove, wv, block, rows=(r0, r1), want_mag=True)
+        say("output head", hd, "worst", check_product(host(O[hd, r0:r1]), o_ref[r0:r1], o_mag[r0:r1], "output"))
+
+
 # ----------------------------------------------------------------------------------------------
 # The block-scaled matrix-core layout (block 32 / 64) and the product kernel that reads it
 # ----------------------------------------------------------------------------------------------
