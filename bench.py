@@ -204,8 +204,8 @@ def main():
                 xd = torch.from_numpy(x).to(dev)
                 scratch = torch.zeros(mx.mx_packed_bytes(1, M, dc.K, fa, LF), dtype=torch.uint8, device=dev)
                 y = torch.empty((M, dc.N), dtype=torch.float32, device=dev)
-                ms = time_launches(lambda i: mx.mx_linear(xd, M, dc.K, dc.K, fa, scratch, Bs[i % nring],
-                                                          dc.N, fb, LF, y, dc.N), 2 * nring)
+                calls = [mx.bound("mx_linear", xd, M, dc.K, dc.K, fa, scratch, Bw, dc.N, fb, LF, y, dc.N) for Bw in Bs]
+                ms = time_launches(lambda i: calls[i % nring](), 2 * nring)
                 nbytes = 0.5625 * dc.N * dc.K + 4 * M * dc.K + 4 * M * dc.N
                 kernels["linear_%s_M%d" % (dc.name, M)] = {
                     "GBps": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),

@@ -300,13 +300,17 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
                     const int c = idx / UPC, d = (idx - c * UPC) * UD;
                     const uint8_t* rec = Abase + (int64_t)c * g.recordA;
                     const uint8_t* src;
+                    int row;                                  // first row the unit belongs to
                     if (d < 16 * kDwA) {
                         const int l16 = d / kDwA, dd = d - l16 * kDwA;
-                        src = rec + ((l16 >> 3) * 32 + (l16 & 7)) * (kDwA * 4) + dd * 4;
+                        row = l16 & 7;
+                        src = rec + ((l16 >> 3) * 32 + row) * (kDwA * 4) + dd * 4;
                     } else {
-                        src = rec + 64 * (kDwA * 4) + (d - 16 * kDwA) * 4;
+                        row = d - 16 * kDwA;
+                        src = rec + 64 * (kDwA * 4) + row * 4;
                     }
-                    load_dwords<UD>(src, v[u]);
+                    // rows >= M feed accumulator rows that are never stored: their slots keep whatever LDS holds
+                    if (row < g.M) load_dwords<UD>(src, v[u]);
                 }
             }
         };
@@ -391,7 +395,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_stream_kernel(GemmArgs g) {
     }
 }
 
-constexpr int kStreamDepth = 8;
+constexpr int kStreamDepth = 5;
 
 template <int WA, int WB, int B, int MR, int NW>
 mx_status launch_stream(const GemmArgs& g, int64_t batch, size_t smem, hipStream_t st) {

@@ -176,6 +176,28 @@ def mx_linear(x, M, K, row_stride, fx, A_scratch, B_packed, N, fb, layout, Y, ld
     return s
 
 
+def bound(name: str, *args, stream=None):
+    """Marshal the arguments of entry point ``name`` once and return a zero-argument callable that
+    issues exactly that call again (status checked).  For loops that launch the same call many times:
+    per-call marshalling costs several microseconds, more than a small kernel runs.  The tensors must
+    stay alive, and the stream current at binding time is the one used."""
+    fn = getattr(load(), name)
+    cargs = []
+    for a in args:
+        if a is None or isinstance(a, torch.Tensor):
+            cargs.append(_p(a))
+        else:
+            cargs.append(a)
+    cargs.append(_stream(stream))
+    cargs = tuple(cargs)
+
+    def call():
+        s = fn(*cargs)
+        if s != MX_OK:
+            raise MxError(s, name)
+    return call
+
+
 # ---- conveniences that only allocate outputs with torch and call the entry points above -----------
 def quantize(x: torch.Tensor, f: mx_format, axis: int = 1) -> Tuple[torch.Tensor, torch.Tensor]:
     """x: float32 CUDA tensor [rows, cols] or [batch, rows, cols] with contiguous columns."""

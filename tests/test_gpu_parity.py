@@ -402,6 +402,28 @@ def test_attention_shaped_products_mixed_widths(seed):
         check_product(host(O)[hd], o_ref, o_mag, "output head %d" % hd)
 
 
+def test_bound_call_matches_direct_call():
+    """mx.bound marshals once and re-issues the same entry-point call: same bytes as the direct call."""
+    case = inputs.llama13b_decode(1)[0]
+    x, wt = inputs.make(case)
+    fa, fb = mx.fmt(case.block, case.wx), mx.fmt(case.block, case.ww)
+    bm, be = mx.quantize(dev(wt), fb)
+    B = mx.pack(bm, be, 1, case.N, case.K, fb)
+    xd = dev(x)
+    scratch = torch.zeros(mx.mx_packed_bytes(1, 1, case.K, fa), dtype=torch.uint8, device=DEV)
+    y1 = torch.zeros((1, case.N), dtype=torch.float32, device=DEV)
+    y2 = torch.zeros_like(y1)
+    mx.mx_linear(xd, 1, case.K, case.K, fa, scratch, B, case.N, fb, mx.MX_LAYOUT_FRAGMENT, y1, case.N)
+    call = mx.bound("mx_linear", xd, 1, case.K, case.K, fa, scratch, B, case.N, fb, mx.MX_LAYOUT_FRAGMENT, y2, case.N)
+    call()
+    call()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(y1), host(y2))
+    bad = mx.bound("mx_linear", xd, 1, case.K + 1, case.K, fa, scratch, B, case.N, fb, mx.MX_LAYOUT_FRAGMENT, y2, case.N)
+    with pytest.raises(mx.MxError):
+        bad()
+
+
 def test_attention_full_size_sampled_heads_and_rows():
     """The attention workload at its full size (32 heads, 2048 positions, head dimension 128) through the
     fused quantize+pack path the benchmark times; the oracle computes two heads on a 32-row window."""
