@@ -215,11 +215,12 @@ def main():
         # mixed-precision attention, 32 heads x 2048 positions x 128: both products are bound by the fp32
         # score matrix (written by Q K^T, read again to quantize P); algorithmic bytes per step below
         heads, seq, dim, ablock = 32, 2048, 128, 16
+        LA = L          # block 16 on the matrix layout is the bfloat16 form; --layout fragment times the int8 path
         wq, wk, wp, wv = inputs.attention_widths(0)
         Qh, Kh, Vh = inputs.attention_qkv(0, heads, seq, dim)
         fq, fk, fpp, fv = (mx.fmt(ablock, w_) for w_ in (wq, wk, wp, wv))
         Qd, Kd, Vd = (torch.from_numpy(t).to(dev) for t in (Qh, Kh, Vh))
-        pb = lambda r, c_, f_: mx.mx_packed_bytes(heads, r, c_, f_, LF)
+        pb = lambda r, c_, f_: mx.mx_packed_bytes(heads, r, c_, f_, LA)
         Aq = torch.empty(pb(seq, dim, fq), dtype=torch.uint8, device=dev)
         Bk = torch.empty(pb(seq, dim, fk), dtype=torch.uint8, device=dev)
         Ap = torch.empty(pb(seq, seq, fpp), dtype=torch.uint8, device=dev)
@@ -228,9 +229,9 @@ def main():
         vexps = torch.empty(mx.mx_exps_bytes(heads, dim, seq, fv), dtype=torch.uint8, device=dev)
         Ss = [torch.empty((heads, seq, seq), dtype=torch.float32, device=dev) for _ in range(2)]
         Od = torch.empty((heads, seq, dim), dtype=torch.float32, device=dev)
-        mx.mx_quantize_pack(Qd, heads, seq, dim, dim, seq * dim, fq, LF, Aq)
-        mx.mx_quantize_pack(Kd, heads, seq, dim, dim, seq * dim, fk, LF, Bk)
-        mx.mx_gemm(heads, seq, seq, dim, Aq, fq, Bk, fk, LF, Ss[0], seq, seq * seq)
+        mx.mx_quantize_pack(Qd, heads, seq, dim, dim, seq * dim, fq, LA, Aq)
+        mx.mx_quantize_pack(Kd, heads, seq, dim, dim, seq * dim, fk, LA, Bk)
+        mx.mx_gemm(heads, seq, seq, dim, Aq, fq, Bk, fk, LA, Ss[0], seq, seq * seq)
         Ps = [torch.softmax(Ss[0] / dim ** 0.5, dim=-1).contiguous()]
         Ps.append(Ps[0].flip(0).contiguous())
         dens = lambda f_: f_.mant_bits / 8 + 1 / f_.block
@@ -243,16 +244,16 @@ def main():
             kernels["attention_w%d%d%d%d_%s" % (wq, wk, wp, wv, name)] = e
 
         n_el = heads * seq * dim
-        ms = time_launches(lambda i: mx.mx_quantize_pack(Qd, heads, seq, dim, dim, seq * dim, fq, LF, Aq), 20)
+        ms = time_launches(lambda i: mx.mx_quantize_pack(Qd, heads, seq, dim, dim, seq * dim, fq, LA, Aq), 20)
         attn_entry("quantize_pack_q", ms, n_el * 4 + Aq.numel())
-        ms = time_launches(lambda i: mx.mx_gemm(heads, seq, seq, dim, Aq, fq, Bk, fk, LF, Ss[i % 2], seq, seq * seq), 10)
+        ms = time_launches(lambda i: mx.mx_gemm(heads, seq, seq, dim, Aq, fq, Bk, fk, LA, Ss[i % 2], seq, seq * seq), 10)
         attn_entry("scores_gemm", ms, Aq.numel() + Bk.numel() + 4 * heads * seq * seq, 2.0 * heads * seq * seq * dim)
-        ms = time_launches(lambda i: mx.mx_quantize_pack(Ps[i % 2], heads, seq, seq, seq, seq * seq, fpp, LF, Ap), 10)
+        ms = time_launches(lambda i: mx.mx_quantize_pack(Ps[i % 2], heads, seq, seq, seq, seq * seq, fpp, LA, Ap), 10)
         attn_entry("quantize_pack_p", ms, 4 * heads * seq * seq + Ap.numel())
         ms = time_launches(lambda i: mx.mx_quantize(Vd, heads, seq, dim, dim, seq * dim, 0, fv, vmant, vexps), 20)
         attn_entry("quantize_v_along_seq", ms, n_el * (4 + dens(fv)))
-        mx.mx_pack(vmant, vexps, heads, dim, seq, fv, LF, Bv)
-        ms = time_launches(lambda i: mx.mx_gemm(heads, seq, dim, seq, Ap, fpp, Bv, fv, LF, Od, dim, seq * dim), 10)
+        mx.mx_pack(vmant, vexps, heads, dim, seq, fv, LA, Bv)
+        ms = time_launches(lambda i: mx.mx_gemm(heads, seq, dim, seq, Ap, fpp, Bv, fv, LA, Od, dim, seq * dim), 10)
         attn_entry("output_gemm", ms, Ap.numel() + Bv.numel() + 4 * n_el, 2.0 * heads * seq * seq * dim)
         del Ss, Ps, Ap
 

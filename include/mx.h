@@ -70,13 +70,21 @@ typedef enum { MX_OK = 0, MX_ERR_BAD_ARG = 1, MX_ERR_UNSUPPORTED = 2, MX_ERR_DEV
  *       density of the canonical form (Eq. 1), arranged in the order the matrix
  *       cores' lanes consume it.  Rows are padded to a multiple of 32 and columns to
  *       a multiple of 4 blocks with zeros.  Either operand of mx_gemm, any M, block 16, 32 or 64.
- *   MX_LAYOUT_MATRIX: the operand as the block-scaled matrix cores of gfx950 read it (block 32 or
- *       64 only): every mantissa is carried exactly in 6-bit float codes, one code for up to 4
- *       stored bits and two codes (q = 16*h + l) for 5..8 bits, i.e. 6 or 12 bits per element plus the
- *       exponent bytes; rows are padded to 32 (64 for one-code operands) and K to 256.  This is the
- *       layout of the compute-bound (prefill) path.  Restriction: exponent bytes above 250
- *       (|x| >= 2^124 at e = 8) are not representable next to the +4 offset of the high code; such
- *       blocks give unspecified products.  Both operands of one mx_gemm use the same layout.
+ *   MX_LAYOUT_MATRIX: the operand as the floating-point matrix cores of gfx950 read it; the
+ *       layout of the compute-bound (prefill, attention) path.  Both operands of one mx_gemm use
+ *       the same layout.
+ *       Block 32 or 64 (block-scaled matrix instruction): every mantissa is carried exactly in 6-bit
+ *       float codes, one code for up to 4 stored bits and two codes (q = 16*h + l) for 5..8 bits,
+ *       i.e. 6 or 12 bits per element plus the exponent bytes; rows are padded to 32 (64 for
+ *       one-code operands) and K to 256.  Restriction: exponent bytes above 250 (|x| >= 2^124 at
+ *       e = 8) are not representable next to the +4 offset of the high code; such blocks give
+ *       unspecified products.
+ *       Block 16 (that instruction scales runs of 32, not 16): every element is stored as the
+ *       bfloat16 number mantissa * 2^exponent, which is exact, 16 bits per element plus the
+ *       exponent bytes; rows are padded to 32 and K to 64.  Restriction: nonzero elements must be
+ *       normal bfloat16 numbers, i.e. at e = 8 the exponent byte of a block with nonzero mantissas
+ *       lies in [mant_bits - 1, 253] (always so for blocks quantized from |x| >= 2^-120); other
+ *       blocks give unspecified products and do not survive mx_unpack.
  */
 enum { MX_LAYOUT_FRAGMENT = 0, MX_LAYOUT_MATRIX = 1 };
 

@@ -6,6 +6,7 @@
 // every dword are stored in the order e0 e4 e1 e5 e2 e6 e3 e7, so that (d << 4) & 0xF0F0F0F0 and
 // d & 0xF0F0F0F0 are the two int8x4 words (times 16) in element order.
 #include "mx_common.h"
+#include "mx_bf16.h"
 #include "mx_matrix.h"
 
 namespace mx {
@@ -136,6 +137,7 @@ using namespace mx;
 
 extern "C" size_t mx_packed_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f, int32_t layout) {
     if (check_pack_args(batch, rows, cols, f, layout) != MX_OK) return 0;
+    if (layout == MX_LAYOUT_MATRIX && f.block == 16) return (size_t)(batch * bf_geom(rows, cols).matrix);
     if (layout == MX_LAYOUT_MATRIX) return (size_t)(batch * mat_geom(rows, cols, f.mant_bits).matrix);
     return (size_t)(batch * frag_geom(rows, cols, f.block, f.mant_bits).matrix);
 }

@@ -277,10 +277,19 @@ mx_status launch_qpack(const QPackArgs& a, int64_t batch, int rnd, hipStream_t s
 
 }  // namespace
 
-bool matrix_format_ok(const mx_format& f) { return format_ok_quant(f) && (f.block == 32 || f.block == 64); }
+// defined in mx_pack_bf16.hip: blocks of 16 use the bfloat16 form of the layout
+mx_status pack_bf16(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
+                    mx_format f, uint8_t* packed, bool pack, hipStream_t st);
+mx_status quantize_pack_bf16(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                             int64_t batch_stride, mx_format f, uint8_t* packed, hipStream_t st);
+
+bool matrix_format_ok(const mx_format& f) {
+    return format_ok_quant(f) && (f.block == 16 || f.block == 32 || f.block == 64);
+}
 
 mx_status pack_matrix(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
                       mx_format f, uint8_t* packed, bool pack, hipStream_t st) {
+    if (f.block == 16) return pack_bf16(mant, exps, batch, rows, cols, f, packed, pack, st);
     MatPackArgs a;
     a.mant = const_cast<uint8_t*>(mant); a.exps = const_cast<uint8_t*>(exps); a.packed = packed;
     a.rows = rows; a.cols = cols; a.g = mat_geom(rows, cols, f.mant_bits);
@@ -300,6 +309,7 @@ mx_status pack_matrix(const uint8_t* mant, const uint8_t* exps, int64_t batch, i
 
 mx_status quantize_pack_matrix(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
                                int64_t batch_stride, mx_format f, uint8_t* packed, hipStream_t st) {
+    if (f.block == 16) return quantize_pack_bf16(x, batch, rows, cols, row_stride, batch_stride, f, packed, st);
     if (((uintptr_t)x & 15) || (row_stride & 3) || (batch_stride & 3)) return MX_ERR_UNSUPPORTED;
     QPackArgs a;
     a.x = x; a.packed = packed; a.rows = rows; a.cols = cols;

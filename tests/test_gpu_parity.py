@@ -458,14 +458,17 @@ def test_attention_full_size_sampled_heads_and_rows():
 MAT = mx.MX_LAYOUT_MATRIX
 
 
-@pytest.mark.parametrize("block,w", [(32, 2), (32, 3), (32, 4), (32, 5), (32, 6), (32, 7), (32, 8), (64, 4), (64, 8)])
+@pytest.mark.parametrize("block,w", [(32, 2), (32, 3), (32, 4), (32, 5), (32, 6), (32, 7), (32, 8), (64, 4), (64, 8),
+                                     (16, 2), (16, 3), (16, 4), (16, 5), (16, 6), (16, 7), (16, 8)])
 def test_matrix_pack_unpack_roundtrip(block, w):
     rng = np.random.default_rng(200 + block + w)
     f = mx.fmt(block, w)
-    for rows, cols in [(70, 5 * 64), (32, 64), (1, 64), (129, 9 * 64)]:
-        # every code, including -2^(w-1); exponent bytes up to the layout's limit of 250
+    for rows, cols in [(70, 5 * 64), (32, 64), (1, 64), (129, 9 * 64), (33, 7 * 16)][:5 if block == 16 else 4]:
+        # every code, including -2^(w-1); exponent bytes over the layout's range: up to 250 for the
+        # block-scaled form, [w - 1, 253] for the bfloat16 form of block 16
+        lo, hi = (w - 1, 254) if block == 16 else (0, 251)
         mant = rng.integers(0, 256, size=mx.mx_mant_bytes(2, rows, cols, f)).astype(np.uint8)
-        exps = rng.integers(0, 251, size=mx.mx_exps_bytes(2, rows, cols, f)).astype(np.uint8)
+        exps = rng.integers(lo, hi, size=mx.mx_exps_bytes(2, rows, cols, f)).astype(np.uint8)
         packed = mx.pack(dev(mant), dev(exps), 2, rows, cols, f, MAT)
         m2, e2 = mx.unpack(packed, 2, rows, cols, f, MAT)
         torch.cuda.synchronize()
@@ -477,8 +480,6 @@ def test_matrix_pack_unpack_roundtrip(block, w):
                                               (32, 3, mx.MX_RTZ), (64, 8, mx.MX_RNE), (32, 5, mx.MX_RNE),
                                               (16, 8, mx.MX_RNE), (16, 4, mx.MX_RTZ), (16, 7, mx.MX_RNE)])
 def test_quantize_pack_equals_quantize_then_pack(layout, block, w, rounding):
-    if layout == MAT and block == 16:
-        pytest.skip("the matrix layout needs blocks of 32 or 64")
     rng = np.random.default_rng(300 + block + w)
     f = mx.fmt(block, w, 8, rounding)
     for batch, rows, cols in [(1, 70, 5 * 64), (2, 33, 8 * 64), (1, 256, 1024)]:
@@ -509,7 +510,7 @@ def test_matrix_gemm_llama7b_full_size_sampled_rows(idx):
         run_case(case, rows=(1000, 1048), layout=MAT, fused=True))
 
 
-@pytest.mark.parametrize("block", [32, 64])
+@pytest.mark.parametrize("block", [16, 32, 64])
 @pytest.mark.parametrize("spread", ["llm", "adversarial"])
 def test_matrix_gemm_all_width_pairs_ragged_shapes(block, spread):
     """Random mantissas and independent random block exponents (within 8 binades, and over 50 binades):
@@ -554,6 +555,67 @@ def test_matrix_gemm_tiles_batch_wide_exponents(M, N):
         y_ref, mag = orc.gemm(qa[b], ea[b], 8, qb[b], eb[b], 4, block, want_mag=True)
         me = product_magnitude(qa[b], ea[b], 8, qb[b], eb[b], 4, block)
         check_product(host(y)[b], y_ref, mag, "matrix batch %d" % b, me)
+
+
+def test_matrix_gemm_block16_workloads_full_output():
+    """Block 16 in the matrix layout (bfloat16 form): the single linear and the OPT-125M layer, whole
+    outputs, through mx_quantize + mx_pack and through the fused mx_quantize_pack."""
+    for case in inputs.single_linear() + inputs.opt125m_layer():
+        say("matrix gemm b16", case.name, "worst", run_case(case, layout=MAT),
+            "fused", run_case(case, layout=MAT, fused=True))
+
+
+@pytest.mark.parametrize("M,N", [(300, 520), (257, 130), (64, 64)])
+def test_matrix_gemm_block16_tiles_batch_wide_exponents(M, N):
+    """Block 16: several workgroup tiles with ragged edges, a batch, K that is not a multiple of the
+    K step, exponent bytes over the bfloat16 form's range, every block term inside fp32."""
+    rng = np.random.default_rng(M + N + 16)
+    K, block, batch = 7 * 64 + 16, 16, 2
+    qa = np.stack([random_operand(rng, M, K, block, 8, 0, 1)[0] for _ in range(batch)])
+    qb = np.stack([random_operand(rng, N, K, block, 4, 0, 1)[0] for _ in range(batch)])
+    base = rng.integers(10, 245, size=(batch, 1, K // block))
+    ea = (base + rng.integers(-3, 4, size=(batch, M, K // block))).clip(7, 253).astype(np.uint8)
+    eb = (254 - base + rng.integers(-3, 4, size=(batch, N, K // block))).clip(7, 253).astype(np.uint8)
+    A, fa = gpu_operand(qa, ea, block, 8, batch, MAT)
+    B, fb = gpu_operand(qb, eb, block, 4, batch, MAT)
+    y = mx.gemm(A, fa, B, fb, M, N, K, batch=batch, layout=MAT)
+    y0 = mx.gemm(A, fa, B, fb, M, N, 0, batch=batch, layout=MAT)
+    y2 = mx.gemm(A, fa, B, fb, M, N, K, batch=batch, layout=MAT)
+    torch.cuda.synchronize()
+    assert not host(y0).any()
+    assert torch.equal(y, y2)
+    for b in range(batch):
+        y_ref, mag = orc.gemm(qa[b], ea[b], 8, qb[b], eb[b], 4, block, want_mag=True)
+        me = product_magnitude(qa[b], ea[b], 8, qb[b], eb[b], 4, block)
+        check_product(host(y)[b], y_ref, mag, "matrix b16 batch %d" % b, me)
+
+
+def test_matrix_attention_full_size_sampled_heads_and_rows():
+    """The attention workload at full size on the matrix layout (block 16, bfloat16 form), fused
+    quantize+pack for Q, K, P and quantize along the sequence + pack for V."""
+    heads, seq, dim, block, seed = 32, 2048, 128, 16, 0
+    wq, wk, wp, wv = inputs.attention_widths(seed)
+    Q, K, V = inputs.attention_qkv(seed, heads, seq, dim)
+    fq, fk, fp_, fv = (mx.fmt(block, w) for w in (wq, wk, wp, wv))
+    A = mx.quantize_pack(dev(Q), fq, MAT)
+    B = mx.quantize_pack(dev(K), fk, MAT)
+    S = mx.gemm(A, fq, B, fk, seq, seq, dim, batch=heads, layout=MAT)
+    P = torch.softmax(S / np.sqrt(dim), dim=-1).contiguous()
+    A2 = mx.quantize_pack(P, fp_, MAT)
+    vm, ve = mx.quantize(dev(V), fv, axis=0)
+    B2 = mx.pack(vm, ve, heads, dim, seq, fv, MAT)
+    O = mx.gemm(A2, fp_, B2, fv, seq, dim, seq, batch=heads, layout=MAT)
+    torch.cuda.synchronize()
+    r0, r1 = 1500, 1532
+    for hd in (0, 31):
+        oq, oqe = orc.quantize(Q[hd], block, wq)
+        ok, oke = orc.quantize(K[hd], block, wk)
+        s_ref, s_mag = orc.gemm(oq, oqe, wq, ok, oke, wk, block, rows=(r0, r1), want_mag=True)
+        say("scores head", hd, "worst", check_product(host(S[hd, r0:r1]), s_ref[r0:r1], s_mag[r0:r1], "scores"))
+        op, ope = orc.quantize(host(P[hd]), block, wp)
+        ov, ove = orc.quantize(V[hd], block, wv, axis=0)
+        o_ref, o_mag = orc.gemm(op, ope, wp, ov, ove, wv, block, rows=(r0, r1), want_mag=True)
+        say("output head", hd, "worst", check_product(host(O[hd, r0:r1]), o_ref[r0:r1], o_mag[r0:r1], "output"))
 
 
 def test_matrix_gemm_identity_and_determinism():
