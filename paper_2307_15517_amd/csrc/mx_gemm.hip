@@ -5,6 +5,8 @@ namespace mx {
 bool matrix_format_ok(const mx_format& f);
 mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, mx_format fa, const void* B,
                       mx_format fb, float* Y, int64_t ldy, int64_t batch_stride_y, hipStream_t st);
+mx_status gemm_bf16(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, const void* B, float* Y,
+                    int64_t ldy, int64_t batch_stride_y, hipStream_t st);
 }  // namespace mx
 
 namespace mx {
@@ -41,6 +43,8 @@ extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, con
     if (K > 0 && (!A_packed || !B_packed)) return MX_ERR_BAD_ARG;
     if (((uintptr_t)A_packed & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
     if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    if (layout == MX_LAYOUT_MATRIX && fa.block == 16)      // bfloat16 form of the layout
+        return gemm_bf16(batch, M, N, K, A_packed, B_packed, Y, ldy, batch_stride_y, (hipStream_t)stream);
     if (layout == MX_LAYOUT_MATRIX)
         return gemm_scaled(batch, M, N, K, A_packed, fa, B_packed, fb, Y, ldy, batch_stride_y, (hipStream_t)stream);
     const FragGeom ga = frag_geom(M, K, fa.block, fa.mant_bits);

@@ -342,14 +342,9 @@ mx_status pick_tile(ScaledArgs& g, int64_t batch, hipStream_t st) {
 
 }  // namespace
 
-// defined in mx_gemm_bf16.hip
-mx_status gemm_bf16(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, const void* B, float* Y,
-                    int64_t ldy, int64_t batch_stride_y, hipStream_t st);
-
 mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, mx_format fa,
                       const void* B, mx_format fb, float* Y, int64_t ldy, int64_t batch_stride_y,
                       hipStream_t st) {
-    if (fa.block == 16) return gemm_bf16(batch, M, N, K, A, B, Y, ldy, batch_stride_y, st);
     const MatGeom ga = mat_geom(M, K, fa.mant_bits), gb = mat_geom(N, K, fb.mant_bits);
     ScaledArgs g;
     g.A = (const uint8_t*)A; g.B = (const uint8_t*)B; g.Y = Y; g.M = M; g.N = N;
