@@ -45,6 +45,22 @@ def test_size_accounting_matches_eq1(lib):
     assert mx.mx_mant_bytes(1, 4, 64, mx.fmt(12, 4)) == 0             # bad block
 
 
+def test_matrix_layout_size_accounting(lib):
+    M = mx.MX_LAYOUT_MATRIX
+    # block 32/64: 6-bit codes, one per element up to 4 stored bits, two above, + one scale byte per 32 elements
+    assert mx.mx_packed_bytes(1, 2048, 4096, mx.fmt(32, 8), M) == 2048 * 4096 * (12 / 8 + 1 / 32)
+    assert mx.mx_packed_bytes(1, 4096, 4096, mx.fmt(32, 4), M) == 4096 * 4096 * (6 / 8 + 1 / 32)
+    assert mx.mx_packed_bytes(1, 4096, 4096, mx.fmt(64, 4), M) == 4096 * 4096 * (6 / 8 + 1 / 32)
+    # block 16: one bfloat16 per element + the exponent bytes, whatever the width
+    for w in (2, 5, 8):
+        assert mx.mx_packed_bytes(1, 2048, 2048, mx.fmt(16, w), M) == 2048 * 2048 * (2 + 1 / 16)
+    # padding: rows to 32, K to 64 elements; the exponent bytes cover the logical rows only
+    assert mx.mx_packed_bytes(1, 33, 48, mx.fmt(16, 4), M) == 64 * 64 * 2 + 256      # 33*3 = 99 bytes, rounded up to 256
+    assert mx.mx_packed_bytes(2, 33, 48, mx.fmt(16, 4), M) == 2 * (64 * 64 * 2 + 256)
+    assert mx.mx_packed_bytes(1, 32, 40, mx.fmt(16, 4), M) == 0                      # cols not a whole number of blocks
+    assert mx.mx_packed_bytes(1, 32, 64, mx.fmt(8, 4), M) == 0                       # block 8 has no matrix layout
+
+
 def test_bad_arguments_are_rejected_before_any_launch(lib):
     f = mx.fmt(32, 8)
     q = lambda **kw: mx.mx_quantize(kw.get("x", 256), 1, kw.get("rows", 4), kw.get("cols", 64),
