@@ -67,7 +67,7 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); the path has no multi-GPU part",
+        print("bench.py: this library runs on one GPU only (--gpus 1); the path has no multi-GPU part",
               file=sys.stderr)
         sys.exit(2)
 
