@@ -243,6 +243,86 @@ int mxo_gemm_at(const int8_t *qa_row, const uint8_t *ea_row, int wa, const int8_
     return mxo_gemm(qa_row, ea_row, wa, qb_row, eb_row, wb, 1, 1, K, block, e, 0, 1, y, mag);
 }
 
+/*
+ * Cast between two precisions of the same MXInt block shape without leaving
+ * the format (Section 4, paragraph on mixed-precision quantization: casting
+ * mantissas is bit extension or truncation, the exponent needs a shift).
+ *
+ * Reading taken here: the cast gives exactly what quantizing the block's exact
+ * values to the destination format gives.  In integers: with mx = max |q_i| and
+ * p = floor(log2 mx), the block maximum is mx * 2^(E - (ws-2)), so the new
+ * shared exponent is E' = E - (ws-2) + p (clamped to the destination's e-bit
+ * range), and every mantissa is q_i * 2^sh in units of the destination,
+ * sh = (E - (ws-2)) - (E' - (wd-2)): a left shift when sh >= 0 (extension,
+ * exact), a right shift by -sh with the destination's rounding (to nearest,
+ * ties to even; or truncation toward zero) otherwise, then saturation at
+ * +-qmax.  A block of zeros stores exponent byte 0.
+ */
+static int mxo_floor_log2(int v) {      /* v >= 1 */
+    int p = 0;
+    while (v > 1) { v >>= 1; ++p; }
+    return p;
+}
+
+int mxo_cast(const int8_t *q, const uint8_t *exps, int64_t rows, int64_t cols, int block, int es,
+             int ws, int ed, int wd, int rounding, int8_t *q_out, uint8_t *exps_out) {
+    if (mxo_check_format(block, es, ws, 0) != MXO_OK) return MXO_BAD_ARG;
+    if (mxo_check_format(block, ed, wd, rounding) != MXO_OK) return MXO_BAD_ARG;
+    if (rows < 0 || cols < 0 || cols % block != 0) return MXO_BAD_ARG;
+    const int64_t nb = cols / block;
+    const int bias_s = mxo_bias(es), bias_d = mxo_bias(ed);
+    const int Emin = -bias_d, Emax = ((1 << ed) - 1) - bias_d;
+    const int qmax = (1 << (wd - 1)) - 1;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t b = 0; b < nb; ++b) {
+            const int8_t *src = q + r * cols + b * block;
+            int8_t *dst = q_out + r * cols + b * block;
+            int mx = 0;
+            for (int i = 0; i < block; ++i) {
+                int a = src[i] < 0 ? -(int)src[i] : (int)src[i];
+                if (a > mx) mx = a;
+            }
+            if (mx == 0) {
+                for (int i = 0; i < block; ++i) dst[i] = 0;
+                exps_out[r * nb + b] = 0;
+                continue;
+            }
+            const int E = (int)exps[r * nb + b] - bias_s;
+            int E2 = E - (ws - 2) + mxo_floor_log2(mx);
+            if (E2 < Emin) E2 = Emin;
+            if (E2 > Emax) E2 = Emax;
+            const int sh = (E - (ws - 2)) - (E2 - (wd - 2));
+            for (int i = 0; i < block; ++i) {
+                const int v = src[i];
+                int64_t res;
+                if (sh >= 0) {
+                    res = sh >= 40 ? (v > 0 ? INT64_MAX / 2 : (v < 0 ? -(INT64_MAX / 2) : 0))
+                                   : (int64_t)v * ((int64_t)1 << sh);
+                } else {
+                    const int k = -sh;
+                    const int64_t a = v < 0 ? -(int64_t)v : (int64_t)v;     /* magnitude: both roundings are odd-symmetric */
+                    int64_t m;
+                    if (k >= 40) {
+                        m = 0;
+                    } else {
+                        m = a >> k;                                          /* truncation */
+                        if (rounding == 0) {
+                            const int64_t rem = a - (m << k), half = (int64_t)1 << (k - 1);
+                            if (rem > half || (rem == half && (m & 1))) ++m;  /* nearest, ties to even */
+                        }
+                    }
+                    res = v < 0 ? -m : m;
+                }
+                if (res > qmax) res = qmax;
+                if (res < -qmax) res = -qmax;
+                dst[i] = (int8_t)res;
+            }
+            exps_out[r * nb + b] = (uint8_t)(E2 + bias_d);
+        }
+    }
+    return MXO_OK;
+}
+
 int mxo_set_threads(int n) {
 #ifdef _OPENMP
     if (n > 0) omp_set_num_threads(n);

@@ -54,8 +54,9 @@ def _load():
         lib.mxo_unpack_bits.argtypes = [p, i64, i64, i32, p]
         lib.mxo_gemm.argtypes = [p, p, i32, p, p, i32, i64, i64, i64, i32, i32, i64, i64, p, p]
         lib.mxo_set_threads.argtypes = [i32]
+        lib.mxo_cast.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, i32, p, p]
         for f in (lib.mxo_quantize, lib.mxo_quantize_axis0, lib.mxo_dequantize, lib.mxo_pack_bits,
-                  lib.mxo_unpack_bits, lib.mxo_gemm, lib.mxo_set_threads):
+                  lib.mxo_unpack_bits, lib.mxo_gemm, lib.mxo_set_threads, lib.mxo_cast):
             f.restype = i32
         _lib = lib
     return _lib
@@ -116,6 +117,22 @@ def dequantize(q: np.ndarray, exps: np.ndarray, block: int, w: int, e: int = 8) 
     y = np.empty((rows, cols), np.float64)
     _check(_load().mxo_dequantize(_ptr(q), _ptr(exps), rows, cols, block, e, w, _ptr(y)), "dequantize")
     return y
+
+
+def cast(q: np.ndarray, exps: np.ndarray, block: int, ws: int, wd: int, es: int = 8, ed: int = 8,
+         rounding: int = RNE) -> Tuple[np.ndarray, np.ndarray]:
+    """MXInt (block, es, ws) -> MXInt (block, ed, wd) in integer arithmetic: mantissa extension or
+    rounding shift plus exponent renormalisation (Section 4, mixed-precision paragraph).
+    q int8 [rows, cols], exps uint8 [rows, cols/block]; returns the same shapes."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    exps = np.ascontiguousarray(exps, dtype=np.uint8)
+    rows, cols = q.shape
+    assert exps.shape == (rows, cols // block)
+    q2 = np.empty((rows, cols), np.int8)
+    e2 = np.empty((rows, cols // block), np.uint8)
+    _check(_load().mxo_cast(_ptr(q), _ptr(exps), rows, cols, block, es, ws, ed, wd, rounding, _ptr(q2),
+                            _ptr(e2)), "cast")
+    return q2, e2
 
 
 def pack_bits(q: np.ndarray, w: int) -> np.ndarray:

@@ -64,6 +64,15 @@ def test_handworked_gemm(row):
     assert y[0, 0] == float(val)
 
 
+@pytest.mark.parametrize("row", list(_rows("handworked_cast.txt")))
+def test_handworked_cast(row):
+    qs, eb, es, ws, ed, wd, rnd, qd, eb2 = row
+    qs = np.array([[int(v) for v in qs.split()]], np.int8)
+    q2, e2 = orc.cast(qs, np.array([[int(eb)]], np.uint8), qs.shape[1], int(ws), int(wd), int(es), int(ed), int(rnd))
+    assert q2.tolist() == [[int(v) for v in qd.split()]]
+    assert e2.tolist() == [[int(eb2)]]
+
+
 # ----------------------------------------------------------------------------------------------
 # Brute force with exact rationals: nearest representable value, ties to even, symmetric clamp
 # ----------------------------------------------------------------------------------------------
@@ -383,3 +392,63 @@ def test_linear_matches_float_linear_within_quantization_error():
     ref = x.astype(np.float64) @ wt.astype(np.float64).T
     rel = np.linalg.norm(y - ref) / np.linalg.norm(ref)
     assert 0.01 < rel < 0.2            # 4-bit weights: ~10 % error; not zero, not garbage
+
+
+# ----------------------------------------------------------------------------------------------
+# Width cast: it must equal quantizing the exact values (two independent routes: integer shifts
+# there, exact rationals / the float quantizer here)
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("ws", [2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("wd", [2, 3, 4, 5, 6, 7, 8])
+def test_cast_equals_quantizing_the_exact_values(ws, wd):
+    rng = np.random.default_rng(1000 + 10 * ws + wd)
+    block = 16
+    q = rng.integers(-(2 ** (ws - 1)), 2 ** (ws - 1), size=(40, 4 * block)).astype(np.int8)
+    q[::3] //= 4                                        # blocks that are not normalised
+    q[5] = 0                                            # zero blocks
+    ex = rng.integers(20, 230, size=(40, 4)).astype(np.uint8)        # exact in fp32
+    x = orc.dequantize(q, ex, block, ws)
+    x32 = x.astype(np.float32)
+    assert np.array_equal(x32.astype(np.float64), x)
+    for rounding in (orc.RNE, orc.RTZ):
+        want_q, want_e = orc.quantize(x32, block, wd, 8, rounding)
+        got_q, got_e = orc.cast(q, ex, block, ws, wd, 8, 8, rounding)
+        assert np.array_equal(got_q, want_q) and np.array_equal(got_e, want_e)
+
+
+def test_cast_brute_force_small_blocks():
+    """Exact rationals on every 2-element block of 4-bit mantissas, to 3 and to 6 bits, both roundings."""
+    for wd in (3, 6):
+        for rounding in (orc.RNE, orc.RTZ):
+            for a in range(-8, 8):
+                for b in range(-8, 8):
+                    q = np.array([[a, b]], np.int8)
+                    ex = np.array([[130]], np.uint8)
+                    vals = [Fraction(a) * Fraction(2) ** (3 - 2), Fraction(b) * Fraction(2) ** (3 - 2)]   # E = 3, ws = 4
+                    eb, qs = _brute_block([float(v) for v in vals], wd, 8, rounding)
+                    got_q, got_e = orc.cast(q, ex, 2, 4, wd, 8, 8, rounding)
+                    assert got_q.tolist() == [qs] and got_e.tolist() == [[eb]], (a, b, wd, rounding)
+
+
+def test_cast_invariants():
+    rng = np.random.default_rng(77)
+    block = 32
+    x = (rng.standard_normal((30, 4 * block)) * np.exp2(rng.integers(-20, 20, size=(30, 1)))).astype(np.float32)
+    for w in range(2, 9):
+        q, ex = orc.quantize(x, block, w)
+        same_q, same_e = orc.cast(q, ex, block, w, w)
+        assert np.array_equal(same_q, q) and np.array_equal(same_e, ex)          # identity on quantizer output
+        for wide in range(w, 9):
+            uq, ue = orc.cast(q, ex, block, w, wide)                              # widening is exact ...
+            assert np.array_equal(orc.dequantize(uq, ue, block, wide), orc.dequantize(q, ex, block, w))
+            bq, be = orc.cast(uq, ue, block, wide, w)                             # ... and narrowing back undoes it
+            assert np.array_equal(bq, q) and np.array_equal(be, ex)
+    # narrowing error: at most half a destination unit (nearest), less than one (truncation)
+    q8, e8 = orc.quantize(x, block, 8)
+    for wd in range(2, 8):
+        for rounding, lim in ((orc.RNE, 0.5), (orc.RTZ, 1.0)):
+            nq, ne = orc.cast(q8, e8, block, 8, wd, 8, 8, rounding)
+            unit = np.repeat(np.ldexp(1.0, ne.astype(int) - 127 - (wd - 2)), block, axis=1)
+            err = np.abs(orc.dequantize(nq, ne, block, wd) - orc.dequantize(q8, e8, block, 8))
+            sat = np.abs(nq) == 2 ** (wd - 1) - 1
+            assert np.all(err[~sat] <= lim * unit[~sat]) and np.all(err[sat] <= unit[sat])
