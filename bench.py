@@ -191,6 +191,22 @@ def main():
                     "GBps": round(pbytes / ms / 1e6, 1), "frac_hbm": round(pbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                     "us": round(ms * 1e3, 2), "bytes": int(pbytes)}
             del qring
+        # width cast inside the format, 8 -> 4 bits at the prefill activation shape:
+        # (8 + 4)/8 + 2/block bytes per element
+        c = work[2]["case"]
+        f4 = mx.fmt(c.block, 4)
+        nring = int(1.3e9 // (c.M * c.K)) + 1
+        m8s = [torch.randint(0, 256, (c.M * c.K,), dtype=torch.uint8, device=dev) for _ in range(nring)]
+        e8 = torch.randint(100, 140, (c.M * c.K // c.block,), dtype=torch.uint8, device=dev)
+        m4 = torch.empty(mx.mx_mant_bytes(1, c.M, c.K, f4), dtype=torch.uint8, device=dev)
+        e4 = torch.empty(mx.mx_exps_bytes(1, c.M, c.K, f4), dtype=torch.uint8, device=dev)
+        calls = [mx.bound("mx_cast", m, e8, 1, c.M, c.K, work[2]["fa"], f4, m4, e4) for m in m8s]
+        ms = time_launches(lambda i: calls[i % nring](), 2 * nring)
+        cbytes = c.M * c.K * (1.5 + 2 / c.block)
+        kernels["cast_%dx%d_w8_to_w4_b%d" % (c.M, c.K, c.block)] = {
+            "GBps": round(cbytes / ms / 1e6, 1), "frac_hbm": round(cbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "us": round(ms * 1e3, 2), "bytes": int(cbytes)}
+        del m8s, calls
         # decode linear, LLaMA-13B shapes: 0.5625*N*K + 4*M*K + 4*M*N bytes per call
         for M in (1, 4, 8):
             for dc in inputs.llama13b_decode(M):

@@ -51,7 +51,7 @@ extern "C" {
  */
 typedef struct {
     int32_t block;     /* elements sharing one exponent, consecutive along the reduction axis:
-                          8, 16, 32 or 64 for mx_quantize / mx_dequantize;
+                          8, 16, 32 or 64 for mx_quantize / mx_dequantize / mx_cast;
                           16, 32 or 64 for mx_pack / mx_unpack / mx_gemm / mx_linear */
     int32_t exp_bits;  /* e, 2..8 (the paper fixes 8 for every tensor, Section 4.1) */
     int32_t mant_bits; /* w = m + 1, 2..8; mantissas lie in -(2^(w-1)-1) .. +(2^(w-1)-1) */
@@ -127,6 +127,20 @@ MX_API mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_
  */
 MX_API mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows,
                         int64_t cols, mx_format f, float* y, void* stream);
+
+/*
+ * Width cast inside the format, without going through floating point (Section 4, the paragraph
+ * on mixed-precision quantization: casting mantissas is bit extension or truncation, the
+ * exponent takes a shift): canonical form in format fs -> canonical form in format fd, same
+ * block size, same batch x rows x cols (blocks along the columns).  The result is what
+ * mx_quantize would give on the exact values of the source: per block the shared exponent is
+ * re-derived from the largest mantissa (a block that is not normalised gains mantissa bits), the
+ * mantissas are shifted left (exact) or right with fd.rounding and saturate at +-qmax of fd; the
+ * exponent is clamped to fd.exp_bits.  mant and mant_out 4-byte aligned, dense, distinct buffers
+ * (MX_ERR_BAD_ARG for in-place use or fs.block != fd.block); fs.rounding is ignored.
+ */
+MX_API mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
+                  mx_format fs, mx_format fd, uint8_t* mant_out, uint8_t* exps_out, void* stream);
 
 /* Bytes mx_pack writes for batch x rows x cols in `layout`; 0 on a bad argument. */
 MX_API size_t mx_packed_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f, int32_t layout);

@@ -21,7 +21,7 @@ MX_LAYOUT_FRAGMENT = 0
 MX_LAYOUT_MATRIX = 1
 
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
-           "mx_dequantize", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
+           "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
            "mx_linear")
 
 
@@ -64,13 +64,14 @@ def load() -> ctypes.CDLL:
     lib.mx_exps_bytes.argtypes, lib.mx_exps_bytes.restype = [i64, i64, i64, mx_format], sz
     lib.mx_quantize.argtypes = [vp, i64, i64, i64, i64, i64, i32, mx_format, vp, vp, vp]
     lib.mx_dequantize.argtypes = [vp, vp, i64, i64, i64, mx_format, vp, vp]
+    lib.mx_cast.argtypes = [vp, vp, i64, i64, i64, mx_format, mx_format, vp, vp, vp]
     lib.mx_packed_bytes.argtypes, lib.mx_packed_bytes.restype = [i64, i64, i64, mx_format, i32], sz
     lib.mx_pack.argtypes = [vp, vp, i64, i64, i64, mx_format, i32, vp, vp]
     lib.mx_quantize_pack.argtypes = [vp, i64, i64, i64, i64, i64, mx_format, i32, vp, vp]
     lib.mx_unpack.argtypes = [vp, i64, i64, i64, mx_format, i32, vp, vp, vp]
     lib.mx_gemm.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, i64, i64, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
-    for name in ("mx_quantize", "mx_dequantize", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
+    for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
                  "mx_linear"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -132,6 +133,13 @@ def mx_dequantize(mant, exps, batch, rows, cols, f, y, stream=None, check: bool 
     s = load().mx_dequantize(_p(mant), _p(exps), batch, rows, cols, f, _p(y), _stream(stream))
     if check:
         _raise(s, "mx_dequantize")
+    return s
+
+
+def mx_cast(mant, exps, batch, rows, cols, fs, fd, mant_out, exps_out, stream=None, check: bool = True) -> int:
+    s = load().mx_cast(_p(mant), _p(exps), batch, rows, cols, fs, fd, _p(mant_out), _p(exps_out), _stream(stream))
+    if check:
+        _raise(s, "mx_cast")
     return s
 
 
@@ -219,6 +227,15 @@ def dequantize(mant: torch.Tensor, exps: torch.Tensor, batch: int, rows: int, co
     y = torch.empty((batch, rows, cols), dtype=torch.float32, device=mant.device)
     mx_dequantize(mant, exps, batch, rows, cols, f, y)
     return y
+
+
+def cast(mant: torch.Tensor, exps: torch.Tensor, batch: int, rows: int, cols: int, fs: mx_format,
+         fd: mx_format) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Canonical form in fs -> canonical form in fd (same block size), in integer arithmetic."""
+    mant_out = torch.empty(mx_mant_bytes(batch, rows, cols, fd), dtype=torch.uint8, device=mant.device)
+    exps_out = torch.empty(mx_exps_bytes(batch, rows, cols, fd), dtype=torch.uint8, device=mant.device)
+    mx_cast(mant, exps, batch, rows, cols, fs, fd, mant_out, exps_out)
+    return mant_out, exps_out
 
 
 def pack(mant: torch.Tensor, exps: torch.Tensor, batch: int, rows: int, cols: int, f: mx_format,

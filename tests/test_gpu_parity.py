@@ -161,6 +161,66 @@ def test_pack_unpack_roundtrip(block, w):
 
 
 # ----------------------------------------------------------------------------------------------
+# Width cast inside the format (bit-exact against the oracle's integer cast)
+# ----------------------------------------------------------------------------------------------
+def check_cast(q, ex, block, ws, wd, es=8, ed=8, rounding=mx.MX_RNE, batch=1):
+    rows, cols = q.shape[-2], q.shape[-1]
+    q2 = q.reshape(-1, cols)
+    want_q, want_e = orc.cast(q2, ex.reshape(-1, cols // block), block, ws, wd, es, ed, rounding)
+    fs, fd = mx.fmt(block, ws, es), mx.fmt(block, wd, ed, rounding)
+    mant = dev(orc.pack_bits(q2, ws).reshape(-1))
+    got_m, got_e = mx.cast(mant, dev(ex.reshape(-1)), batch, rows, cols, fs, fd)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(got_e), want_e.reshape(-1)), "exponent bytes differ"
+    assert np.array_equal(host(got_m), orc.pack_bits(want_q, wd).reshape(-1)), "mantissa bytes differ"
+
+
+@pytest.mark.parametrize("block", [8, 16, 32, 64])
+def test_cast_all_width_pairs(block):
+    rng = np.random.default_rng(900 + block)
+    for ws in range(2, 9):
+        for wd in range(2, 9):
+            rows, cols = 37, 5 * 64 + (block if block < 32 else 0)      # for small blocks the tensor ends inside a 32-element run
+            q = rng.integers(-(2 ** (ws - 1)), 2 ** (ws - 1), size=(rows, cols)).astype(np.int8)   # every code
+            q[::4] //= 8                                                # blocks that are not normalised
+            q[3] = 0                                                    # zero blocks
+            ex = rng.integers(0, 256, size=(rows, cols // block)).astype(np.uint8)
+            check_cast(q, ex, block, ws, wd, rounding=mx.MX_RNE if (ws + wd) % 2 else mx.MX_RTZ)
+
+
+def test_cast_exponent_widths_batch_and_workload_shape():
+    rng = np.random.default_rng(950)
+    # narrower and wider exponent fields: clamping on the way down, rebasing on the way up
+    for es, ed in [(8, 4), (4, 8), (8, 2), (5, 7)]:
+        q = rng.integers(-127, 128, size=(2 * 20, 256)).astype(np.int8)
+        ex = rng.integers(0, 2 ** es, size=(2 * 20, 256 // 32)).astype(np.uint8)
+        check_cast(q.reshape(2, 20, 256), ex, 32, 8, 4, es, ed, batch=2)
+    # the prefill activations: 8-bit quantizer output narrowed to 4 bits, and widened back
+    case = inputs.llama7b_prefill()[0]
+    x, _ = inputs.make(case, 512)
+    q8, e8 = orc.quantize(x, case.block, 8)
+    check_cast(q8, e8, case.block, 8, 4)
+    q4, e4 = orc.cast(q8, e8, case.block, 8, 4)
+    check_cast(q4, e4, case.block, 4, 8)
+    # cast of the quantizer's own output on the GPU equals quantizing to the narrow format's grid of the wide values
+    f8, f4 = mx.fmt(case.block, 8), mx.fmt(case.block, 4)
+    m8, x8 = mx.quantize(dev(x), f8)
+    m4, x4 = mx.cast(m8, x8, 1, x.shape[0], x.shape[1], f8, f4)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(m4), orc.pack_bits(q4, 4).reshape(-1)) and np.array_equal(host(x4), e4.reshape(-1))
+
+
+def test_cast_rejects_bad_arguments():
+    f8, f4 = mx.fmt(32, 8), mx.fmt(32, 4)
+    buf = torch.zeros(4096, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(4096, dtype=torch.uint8, device=DEV)
+    assert mx.mx_cast(buf, buf, 1, 4, 64, f8, mx.fmt(16, 4), out, out, check=False) == mx.MX_ERR_BAD_ARG   # block differs
+    assert mx.mx_cast(buf, buf, 1, 4, 64, f8, f4, buf, out, check=False) == mx.MX_ERR_BAD_ARG               # in place
+    assert mx.mx_cast(buf, buf, 1, 4, 48, f8, f4, out, out, check=False) == mx.MX_ERR_BAD_ARG               # cols % block
+    assert mx.mx_cast(buf, buf, 0, 4, 64, f8, f4, out, out, check=False) == mx.MX_OK                        # empty
+
+
+# ----------------------------------------------------------------------------------------------
 def gpu_operand(q, ex, block, w, batch=1, layout=mx.MX_LAYOUT_FRAGMENT):
     f = mx.fmt(block, w)
     rows, cols = q.shape[-2], q.shape[-1]
