@@ -81,17 +81,30 @@ def set_threads(n: int) -> int:
 
 
 def quantize(x: np.ndarray, block: int, w: int, e: int = 8, rounding: int = RNE,
-             axis: int = 1) -> Tuple[np.ndarray, np.ndarray]:
+             axis: int = 1, block_rows: int = 1) -> Tuple[np.ndarray, np.ndarray]:
     """Quantize a 2-D float32 array to MXInt.
 
     axis=1: blocks along each row; returns q int8 [rows, cols], exps uint8 [rows, cols/block].
     axis=0: blocks down each column; returns the quantization of x.T:
             q int8 [cols, rows], exps uint8 [cols, rows/block].
+    block_rows=R > 1 (axis 1 only): the paper's two-dimensional block shape (block, R) of
+            Section 4.1, e.g. MXInt((16,2),8,7): R adjacent rows x block columns share one
+            exponent.  A block is just a set of R*block elements, so the rows are regrouped and
+            the one-dimensional routine is applied; exps is uint8 [rows/R, cols/block].
     """
     x = np.ascontiguousarray(x, dtype=np.float32)
     assert x.ndim == 2
     rows, cols = x.shape
     lib = _load()
+    if block_rows != 1:
+        if axis != 1 or block_rows < 1 or rows % block_rows or block < 1 or cols % block:
+            raise ValueError("two-dimensional blocks need axis 1, rows % block_rows == 0, cols % block == 0")
+        R, nb = block_rows, cols // block
+        # [rows/R, R, nb, block] -> [rows/R, nb, R, block]: every block's elements become one run
+        xr = np.ascontiguousarray(x.reshape(rows // R, R, nb, block).transpose(0, 2, 1, 3)).reshape(rows // R, nb * R * block)
+        qr, ex = quantize(xr, R * block, w, e, rounding)
+        q = np.ascontiguousarray(qr.reshape(rows // R, nb, R, block).transpose(0, 2, 1, 3)).reshape(rows, cols)
+        return q, ex
     if axis == 1:
         if block < 1 or cols % block:
             raise ValueError("cols must be a multiple of block")
@@ -106,6 +119,12 @@ def quantize(x: np.ndarray, block: int, w: int, e: int = 8, rounding: int = RNE,
         rc = lib.mxo_quantize_axis0(_ptr(x), rows, cols, cols, block, e, w, rounding, _ptr(q), _ptr(ex))
     _check(rc, "quantize")
     return q, ex
+
+
+def row_exps(exps: np.ndarray, block_rows: int) -> np.ndarray:
+    """Exponent bytes of a two-dimensional-block tensor [rows/R, nblk] spelled out per row [rows, nblk]
+    (the form dequantize, gemm and cast take)."""
+    return np.repeat(np.ascontiguousarray(exps, dtype=np.uint8), block_rows, axis=0)
 
 
 def dequantize(q: np.ndarray, exps: np.ndarray, block: int, w: int, e: int = 8) -> np.ndarray:

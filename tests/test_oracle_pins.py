@@ -54,6 +54,41 @@ def test_handworked_blocks(row):
         assert orc.pack_bits(q, w).tolist() == [[int(h, 16) for h in hexbytes.split()]]
 
 
+@pytest.mark.parametrize("row", list(_rows("handworked_blocks2d.txt")))
+def test_handworked_two_dimensional_blocks(row):
+    w, rnd, bc, br, xs, ebytes, qs = row
+    x = np.array([[float(v) for v in r.split()] for r in xs.split(";")], np.float32)
+    q, ex = orc.quantize(x, int(bc), int(w), 8, orc.RNE if rnd == "rne" else orc.RTZ, block_rows=int(br))
+    assert ex.reshape(-1).tolist() == [int(v) for v in ebytes.split()]
+    assert q.tolist() == [[int(v) for v in r.split()] for r in qs.split(";")]
+
+
+def test_paper_type_16x2_size_and_structure():
+    """MXInt((16,2),8,7) as the paper writes it (Section 4.1): 16 x 2 elements per exponent, 8.25 bits
+    per element; every exponent covers exactly two adjacent rows and sixteen columns."""
+    rows = {r[0]: r for r in _rows("paper_values.txt")}
+    printed = rows["avg_bits_MXInt_16x2_8_7"][4]
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((6, 64)) * np.exp2(rng.integers(-8, 8, size=(6, 1)))).astype(np.float32)
+    q, ex = orc.quantize(x, 16, 8, block_rows=2)
+    assert ex.shape == (3, 4)
+    assert Fraction(8 * (orc.pack_bits(q, 8).nbytes + ex.nbytes), x.size) == Fraction(printed)
+    for p in range(3):
+        for b in range(4):
+            blk = x[2 * p:2 * p + 2, 16 * b:16 * b + 16]
+            eb, qs = _brute_block(blk.reshape(-1), 8, 8, orc.RNE)
+            assert ex[p, b] == eb and q[2 * p:2 * p + 2, 16 * b:16 * b + 16].reshape(-1).tolist() == qs
+    # one-row blocks of 32 hold the same number of bits but are a different grouping
+    q1, e1 = orc.quantize(x, 32, 8)
+    assert e1.size == ex.size and not np.array_equal(orc.dequantize(q1, e1, 32, 8),
+                                                     orc.dequantize(q, orc.row_exps(ex, 2), 16, 8))
+    # rows that are equal pairwise: the two-row block then is the one-row block
+    xx = np.repeat(x[:3], 2, axis=0)
+    q2, e2 = orc.quantize(xx, 16, 5, block_rows=2)
+    q3, e3 = orc.quantize(xx, 16, 5)
+    assert np.array_equal(q2, q3) and np.array_equal(orc.row_exps(e2, 2), e3)
+
+
 @pytest.mark.parametrize("row", list(_rows("handworked_gemm.txt")))
 def test_handworked_gemm(row):
     qa, ea, wa, qb, eb, wb, val = row
