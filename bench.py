@@ -183,6 +183,15 @@ def main():
             kernels["quantize_%dx%d_w%d_b%d" % (c.M, c.K, c.wx, c.block)] = {
                 "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                 "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
+            if c.K == 11008:
+                # the paper's own block shape: 16 columns x 2 rows per exponent, MXInt((16,2),8,7)
+                f2 = mx.fmt(16, 8, block_rows=2)
+                e2 = torch.empty(mx.mx_exps_bytes(1, c.M, c.K, f2), dtype=torch.uint8, device=dev)
+                ms = time_launches(lambda i: mx.mx_quantize(qring[i % nring], 1, c.M, c.K, c.K, 0, 1, f2,
+                                                            w["mant"], e2), 2 * nring)
+                kernels["quantize_%dx%d_w8_b16x2" % (c.M, c.K)] = {
+                    "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                    "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
             if args.layout == "matrix":
                 ms = time_launches(lambda i: mx.mx_quantize_pack(qring[i % nring], 1, c.M, c.K, c.K, 0, w["fa"], L,
                                                                  w["A"]), 2 * nring)

@@ -47,15 +47,21 @@ extern "C" {
  * One MXInt format (Section 4.1).  The paper writes MXInt(B, e, m) with m the
  * mantissa width WITHOUT the sign bit (Eq. 1: p = e/prod(B) + m + 1); here
  * mant_bits = m + 1 is the stored width of an element, so the paper's
- * MXInt((16,2), 8, 7) has block = 32, exp_bits = 8, mant_bits = 8.
+ * MXInt((16,2), 8, 7) has block = 16, block_rows = 2, exp_bits = 8, mant_bits = 8.
  */
 typedef struct {
-    int32_t block;     /* elements sharing one exponent, consecutive along the reduction axis:
+    int32_t block;     /* elements of a row sharing one exponent, consecutive along the reduction axis:
                           8, 16, 32 or 64 for mx_quantize / mx_dequantize / mx_cast;
                           16, 32 or 64 for mx_pack / mx_unpack / mx_gemm / mx_linear */
     int32_t exp_bits;  /* e, 2..8 (the paper fixes 8 for every tensor, Section 4.1) */
     int32_t mant_bits; /* w = m + 1, 2..8; mantissas lie in -(2^(w-1)-1) .. +(2^(w-1)-1) */
     int32_t rounding;  /* MX_RNE or MX_RTZ */
+    int32_t block_rows;/* 1 or 2: adjacent rows that share the exponent, i.e. the second entry of the
+                          paper's block shape -- MXInt((16,2),8,7) is block 16, block_rows 2, mant_bits 8.
+                          With 2, rows must be even and the canonical exponent array is
+                          [rows/2][cols/block]; the packed layouts repeat the byte for both rows, so
+                          mx_gemm does not care.  Not supported (MX_ERR_UNSUPPORTED): mx_quantize along
+                          axis 0, mx_cast, and the activation format of mx_linear. */
 } mx_format;
 
 enum { MX_RNE = 0,  /* round to nearest, ties to the even mantissa */

@@ -170,6 +170,7 @@ extern "C" mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t b
                              mx_format fs, mx_format fd, uint8_t* mant_out, uint8_t* exps_out, void* stream) {
     if (!format_ok_quant(fs) || !format_ok_quant(fd) || fs.block != fd.block) return MX_ERR_BAD_ARG;
     if (batch < 0 || rows < 0 || cols < 0 || cols % fs.block != 0) return MX_ERR_BAD_ARG;
+    if (fs.block_rows != 1 || fd.block_rows != 1) return MX_ERR_UNSUPPORTED;
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!mant || !exps || !mant_out || !exps_out) return MX_ERR_BAD_ARG;
     if (((uintptr_t)mant & 3) || ((uintptr_t)mant_out & 3)) return MX_ERR_BAD_ARG;

@@ -13,7 +13,8 @@ constexpr int kWave = 64;
 // ---- format checks (host) ------------------------------------------------------------------
 inline bool format_ok_quant(const mx_format& f) {
     return (f.block == 8 || f.block == 16 || f.block == 32 || f.block == 64) && f.exp_bits >= 2 && f.exp_bits <= 8 &&
-           f.mant_bits >= 2 && f.mant_bits <= 8 && (f.rounding == MX_RNE || f.rounding == MX_RTZ);
+           f.mant_bits >= 2 && f.mant_bits <= 8 && (f.rounding == MX_RNE || f.rounding == MX_RTZ) &&
+           (f.block_rows == 1 || f.block_rows == 2);
 }
 inline bool format_ok_gemm(const mx_format& f) {
     return format_ok_quant(f) && (f.block == 16 || f.block == 32 || f.block == 64);

@@ -15,6 +15,7 @@ struct LinQuantArgs {
     int64_t K, row_stride, batch_stride, chunks, matrix_bytes;
     int32_t piece, record, bias, emax;
     int32_t vec;         // x and its strides allow 16-byte loads
+    int32_t brows;       // 2: rows 2p and 2p+1 (adjacent lanes) share their exponents
 };
 
 // One wave per record of the fragment layout (32 rows x 4 blocks); four waves, i.e. four consecutive
@@ -95,6 +96,10 @@ __global__ __launch_bounds__(256) void quantize_to_fragments_kernel(LinQuantArgs
             }
             const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
             am = o > am ? o : am;
+            if (a.brows == 2) {         // two-row blocks: the neighbouring lane holds the other row
+                const uint32_t o2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);
+                am = o2 > am ? o2 : am;
+            }
             const int ef = (int)(am >> 23);
             int E = ef == 0 ? -127 : ef - 127;
             E = E < -a.bias ? -a.bias : E;
@@ -169,6 +174,7 @@ mx_status run_lq(const float* x, int64_t batch, int64_t M, int64_t rows_out, int
     a.bias = (1 << (f.exp_bits - 1)) - 1;
     a.emax = ((1 << f.exp_bits) - 1) - a.bias;
     a.vec = (((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0 && (batch_stride & 3) == 0) ? 1 : 0;
+    a.brows = f.block_rows;
     if (ceil_div(rows_out, 32) * ceil_div(ga.chunks, 4) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     switch (f.block) {
         case 16: MX_SW(f.mant_bits, kW, return (launch_lq<kW, 16>(a, batch, f.rounding, st))); break;
@@ -195,7 +201,7 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
                                int32_t layout, float* Y, int64_t ldy, void* stream) {
     if (!format_ok_quant(fx) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
     if (fx.block != fb.block || fx.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
-    if (!format_ok_gemm(fx)) return MX_ERR_UNSUPPORTED;
+    if (!format_ok_gemm(fx) || fx.block_rows != 1) return MX_ERR_UNSUPPORTED;
     if (layout != MX_LAYOUT_FRAGMENT) return layout == MX_LAYOUT_MATRIX ? MX_ERR_UNSUPPORTED : MX_ERR_BAD_ARG;
     if (M < 0 || N < 0 || K < 0 || K % fx.block != 0 || row_stride < K || ldy < N) return MX_ERR_BAD_ARG;
     if (M > 8) return MX_ERR_UNSUPPORTED;

@@ -50,6 +50,7 @@ struct PackArgs {
     int64_t groups, chunks;
     int64_t matrix_bytes;  // packed bytes per batch entry
     int32_t block, w, piece, record;
+    int32_t brows;         // rows per exponent of the canonical form (1 or 2)
 };
 
 // One thread per (record, lane); grid.y = batch.
@@ -67,7 +68,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a) {
     const int64_t row_bytes = a.cols * a.w / 8;
     const int64_t nblk = a.cols / a.block;
     uint8_t* mant = const_cast<uint8_t*>(a.mant) + b * a.rows * row_bytes;
-    uint8_t* exps = const_cast<uint8_t*>(a.exps) + b * a.rows * nblk;
+    uint8_t* exps = const_cast<uint8_t*>(a.exps) + b * (a.rows / a.brows) * nblk;
     uint8_t* rec_base = a.packed + b * a.matrix_bytes + rec * a.record;
     uint8_t* piece = rec_base + (int64_t)lane * a.piece;
     for (int j = 0; j < 4; ++j) {
@@ -94,8 +95,9 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a) {
         }
         if (h == 0) {
             uint8_t* pe = rec_base + 64 * a.piece + i * 4 + j;
-            if (PACK) *pe = inside ? exps[row * nblk + blk] : (uint8_t)0;
-            else if (inside) exps[row * nblk + blk] = *pe;
+            // two-row blocks: both rows carry the pair's byte in the layout; the even row writes it back
+            if (PACK) *pe = inside ? exps[(row / a.brows) * nblk + blk] : (uint8_t)0;
+            else if (inside && row % a.brows == 0) exps[(row / a.brows) * nblk + blk] = *pe;
         }
     }
 }
@@ -104,7 +106,7 @@ mx_status check_pack_args(int64_t batch, int64_t rows, int64_t cols, const mx_fo
     if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
     if (!format_ok_quant(f)) return MX_ERR_BAD_ARG;
     if (layout == MX_LAYOUT_FRAGMENT ? !format_ok_gemm(f) : !matrix_format_ok(f)) return MX_ERR_UNSUPPORTED;
-    if (batch < 0 || rows < 0 || cols < 0 || cols % f.block != 0) return MX_ERR_BAD_ARG;
+    if (batch < 0 || rows < 0 || cols < 0 || cols % f.block != 0 || rows % f.block_rows != 0) return MX_ERR_BAD_ARG;
     return MX_OK;
 }
 
@@ -123,6 +125,7 @@ mx_status run_pack(const uint8_t* mant, const uint8_t* exps, int64_t batch, int6
     a.mant = mant; a.exps = exps; a.packed = packed;
     a.rows = rows; a.cols = cols; a.groups = g.groups; a.chunks = g.chunks;
     a.matrix_bytes = g.matrix; a.block = f.block; a.w = f.mant_bits; a.piece = g.piece; a.record = g.record;
+    a.brows = f.block_rows;
     const int64_t threads = g.groups * g.chunks * 64;
     dim3 grid((unsigned)ceil_div(threads, 256), (unsigned)batch);
     hipLaunchKernelGGL((pack_kernel<PACK>), grid, dim3(256), 0, (hipStream_t)stream, a);

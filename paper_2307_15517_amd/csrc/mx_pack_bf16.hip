@@ -15,6 +15,7 @@ struct BfPackArgs {
     int64_t rows, cols;
     BfGeom g;
     int32_t w, bias;
+    int32_t brows;      // rows per exponent of the canonical form (1 or 2)
 };
 
 // Mantissa of element k of a canonical row (w-bit two's complement at bit k*w).
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(BfPackArgs a) {
     uint32_t out[4] = {0, 0, 0, 0};
     if (row < a.rows && kf < a.g.nblk) {
         const uint8_t* mrow = a.mant + (b * a.rows + row) * (a.cols * a.w / 8);
-        const uint8_t ebyte = a.exps[(b * a.rows + row) * a.g.nblk + kf];
+        const uint8_t ebyte = a.exps[((b * a.rows + row) / a.brows) * a.g.nblk + kf];
         const int s = (int)ebyte - a.bias - (a.w - 2);
         for (int e = 0; e < 8; ++e) {
             const int q = canon_get(mrow, kf * 16 + 8 * h + e, a.w);
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(256) void unpack_bf16_kernel(BfPackArgs a) {
             while (nbits >= 8) { *out++ = (uint8_t)acc; acc >>= 8; nbits -= 8; }
         }
     }
-    a.exps[(b * a.rows + row) * a.g.nblk + kf] = ebyte;
+    if (row % a.brows == 0) a.exps[((b * a.rows + row) / a.brows) * a.g.nblk + kf] = ebyte;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -93,6 +94,7 @@ struct BfQPackArgs {
     int64_t rows, cols, row_stride, batch_stride;
     BfGeom g;
     int32_t bias, emax;
+    int32_t brows;      // 2: rows 2p and 2p+1 (adjacent lanes) share their exponents
 };
 
 constexpr int kBfRowPitch = 256 + 16;     // bytes; the 16-byte skew spreads the lanes' rows over the banks
@@ -138,6 +140,10 @@ __global__ __launch_bounds__(256) void quantize_pack_bf16_kernel(BfQPackArgs a) 
         }
         const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
         am = o > am ? o : am;
+        if (a.brows == 2) {             // two-row blocks: the neighbouring lane holds the other row
+            const uint32_t o2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);
+            am = o2 > am ? o2 : am;
+        }
         const int ef = (int)(am >> 23);
         int E = ef == 0 ? -127 : ef - 127;
         E = E < -a.bias ? -a.bias : E;
@@ -177,6 +183,7 @@ mx_status pack_bf16(const uint8_t* mant, const uint8_t* exps, int64_t batch, int
     a.mant = const_cast<uint8_t*>(mant); a.exps = const_cast<uint8_t*>(exps); a.packed = packed;
     a.rows = rows; a.cols = cols; a.g = bf_geom(rows, cols);
     a.w = f.mant_bits; a.bias = (1 << (f.exp_bits - 1)) - 1;
+    a.brows = f.block_rows;
     const int64_t threads = pack ? a.g.row_tiles * a.g.ksteps * 2 * 64 : rows * a.g.nblk;
     if (ceil_div(threads, 256) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     dim3 grid((unsigned)ceil_div(threads, 256), (unsigned)batch);
@@ -195,6 +202,7 @@ mx_status quantize_pack_bf16(const float* x, int64_t batch, int64_t rows, int64_
     a.g = bf_geom(rows, cols);
     a.bias = (1 << (f.exp_bits - 1)) - 1;
     a.emax = ((1 << f.exp_bits) - 1) - a.bias;
+    a.brows = f.block_rows;
     if (a.g.row_tiles * ((a.g.ksteps / 2 + 3) / 4) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     switch (f.mant_bits) {
         case 2: return launch_bf_qpack<2>(a, batch, f.rounding, st);

@@ -37,6 +37,7 @@ struct MatPackArgs {
     int64_t rows, cols;
     MatGeom g;
     int32_t block, w, bias;
+    int32_t brows;      // rows per exponent of the canonical form (1 or 2)
 };
 
 // Mantissa of element k of a canonical row (w-bit two's complement at bit k*w).
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(256) void pack_matrix_kernel(MatPackArgs a) {
     }
     // scale byte of this lane's block
     uint8_t sb = 0;
-    if (inside) sb = (uint8_t)((int)a.exps[(b * a.rows + row) * nblk + k0 / a.block] + (127 - a.bias));
+    if (inside) sb = (uint8_t)((int)a.exps[((b * a.rows + row) / a.brows) * nblk + k0 / a.block] + (127 - a.bias));
     base[a.g.frag_bytes + ((rt * (a.g.ksteps / 4) + (ks >> 2)) * 64 + lane) * 4 + (ks & 3)] = sb;
 }
 
@@ -137,9 +138,9 @@ __global__ __launch_bounds__(256) void unpack_matrix_kernel(MatPackArgs a) {
         nbits += a.w;
         while (nbits >= 8) { *out++ = (uint8_t)acc; acc >>= 8; nbits -= 8; }
     }
-    if ((run * 32) % a.block == 0) {
+    if ((run * 32) % a.block == 0 && row % a.brows == 0) {
         const uint8_t sb = base[a.g.frag_bytes + ((rt * (a.g.ksteps / 4) + (ks >> 2)) * 64 + lane) * 4 + (ks & 3)];
-        a.exps[(b * a.rows + row) * nblk + run * 32 / a.block] = (uint8_t)((int)sb - (127 - a.bias));
+        a.exps[((b * a.rows + row) / a.brows) * nblk + run * 32 / a.block] = (uint8_t)((int)sb - (127 - a.bias));
     }
 }
 
@@ -157,6 +158,7 @@ struct QPackArgs {
     int64_t rows, cols, row_stride, batch_stride;
     MatGeom g;
     int32_t bias, emax;
+    int32_t brows;      // 2: rows 2p and 2p+1 (adjacent lanes) share their exponents
 };
 
 constexpr int kQpRowPitch = 256 + 16;     // bytes; the 16-byte skew spreads the lanes' rows over the banks
@@ -206,6 +208,10 @@ __global__ __launch_bounds__(256) void quantize_pack_matrix_kernel(QPackArgs a) 
     }
     if (B == 64) {                      // the two halves of a lane pair form one block
         const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
+        am = o > am ? o : am;
+    }
+    if (a.brows == 2) {                 // two-row blocks: the neighbouring lane holds the other row
+        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);
         am = o > am ? o : am;
     }
     const int ef = (int)(am >> 23);
@@ -294,6 +300,7 @@ mx_status pack_matrix(const uint8_t* mant, const uint8_t* exps, int64_t batch, i
     a.mant = const_cast<uint8_t*>(mant); a.exps = const_cast<uint8_t*>(exps); a.packed = packed;
     a.rows = rows; a.cols = cols; a.g = mat_geom(rows, cols, f.mant_bits);
     a.block = f.block; a.w = f.mant_bits; a.bias = (1 << (f.exp_bits - 1)) - 1;
+    a.brows = f.block_rows;
     if (pack) {
         const int64_t threads = a.g.row_tiles * a.g.ksteps * 64;
         dim3 grid((unsigned)ceil_div(threads, 256), (unsigned)batch);
@@ -317,6 +324,7 @@ mx_status quantize_pack_matrix(const float* x, int64_t batch, int64_t rows, int6
     a.g = mat_geom(rows, cols, f.mant_bits);
     a.bias = (1 << (f.exp_bits - 1)) - 1;
     a.emax = ((1 << f.exp_bits) - 1) - a.bias;
+    a.brows = f.block_rows;
     if (a.g.row_tiles * (a.g.ksteps / 4) > 0x7fffffffLL || batch > 65535) return MX_ERR_UNSUPPORTED;
     if (f.block == 32) { MX_SW(f.mant_bits, kW, return (launch_qpack<kW, 32>(a, batch, f.rounding, st))); }
     else               { MX_SW(f.mant_bits, kW, return (launch_qpack<kW, 64>(a, batch, f.rounding, st))); }

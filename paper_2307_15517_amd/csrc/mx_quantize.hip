@@ -161,6 +161,76 @@ __global__ __launch_bounds__(256) void quantize_axis1_kernel(QuantArgs a) {
     }
 }
 
+// Two-row blocks (the paper's block shape (B, 2), Section 4.1): rows 2p and 2p+1 share the exponents
+// of their blocks.  One lane owns the same 8 consecutive columns of both rows, LPB = B/8 adjacent
+// lanes own one block; items run with the columns fastest, so each row is read in whole segments.
+struct QuantRows2Args {
+    const float* x;
+    uint8_t* mant;
+    uint8_t* exps;
+    int64_t items;         // batch * (rows/2) * (cols/8)
+    int64_t row_octets;    // cols/8
+    int64_t pairs;         // rows/2 per batch entry
+    int64_t row_stride;
+    int64_t batch_stride;
+    int32_t bias;
+    int32_t emax;
+    int32_t vec;           // 16-byte loads are aligned
+};
+
+template <int W, int B, int RND>
+__global__ __launch_bounds__(256) void quantize_rows2_kernel(QuantRows2Args a) {
+    constexpr int LPB = B / 8;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t wave_first = first - (threadIdx.x & 63);
+    for (int64_t wo = wave_first, o = first; wo < a.items; wo += stride, o += stride) {
+        const bool live = o < a.items;
+        const int64_t pr = o / a.row_octets, c8 = o - pr * a.row_octets;      // pair index over the batch, octet
+        const int64_t b = pr / a.pairs, p = pr - b * a.pairs;
+        float v[2][8];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (live) {
+                const float* src = a.x + b * a.batch_stride + (2 * p + r) * a.row_stride + c8 * 8;
+                if (a.vec) {
+                    const float4 lo = reinterpret_cast<const float4*>(src)[0];
+                    const float4 hi = reinterpret_cast<const float4*>(src)[1];
+                    v[r][0] = lo.x; v[r][1] = lo.y; v[r][2] = lo.z; v[r][3] = lo.w;
+                    v[r][4] = hi.x; v[r][5] = hi.y; v[r][6] = hi.z; v[r][7] = hi.w;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[r][i] = src[i];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[r][i] = 0.f;
+            }
+        }
+        uint32_t am = 0;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t ab = __float_as_uint(v[r][i]) & 0x7fffffffu;
+                am = ab > am ? ab : am;
+            }
+        am = group_max_u32<LPB>(am);
+        const int E = block_exponent(am, a.bias, a.emax);
+        const int shift = (W - 2) - E;
+        if (live) {
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                int q[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(v[r][i], shift);
+                store_stream<W>(a.mant + ((pr * 2 + r) * a.row_octets + c8) * W, pack8<W>(q));
+            }
+            if ((threadIdx.x & (LPB - 1)) == 0) a.exps[o / LPB] = (uint8_t)(E + a.bias);
+        }
+    }
+}
+
 struct QuantAxis0Args {
     const float* x;
     uint8_t* mant;
@@ -206,7 +276,9 @@ struct DequantArgs {
     const uint8_t* exps;
     float* y;
     int64_t octets;
+    int64_t row_octets;    // cols/8
     int32_t bias;
+    int32_t block_rows;    // 1 or 2 rows per exponent
 };
 
 template <int W, int B>
@@ -215,7 +287,12 @@ __global__ __launch_bounds__(256) void dequantize_kernel(DequantArgs a) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; o < a.octets; o += stride) {
         const uint64_t s = load_stream<W>(a.mant + o * W);
-        const int sh = (int)a.exps[o / LPB] - a.bias - (W - 2);
+        int64_t eidx = o / LPB;
+        if (a.block_rows == 2) {                    // rows 2p and 2p+1 read the exponents of pair p
+            const int64_t row = o / a.row_octets, c8 = o - row * a.row_octets;
+            eidx = ((row >> 1) * a.row_octets + c8) / LPB;
+        }
+        const int sh = (int)a.exps[eidx] - a.bias - (W - 2);
         float r[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -243,6 +320,17 @@ mx_status launch_axis1(const QuantArgs& a, int rnd, hipStream_t st) {
         hipLaunchKernelGGL((quantize_axis1_kernel<W, B, MX_RNE>), dim3(grid), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL((quantize_axis1_kernel<W, B, MX_RTZ>), dim3(grid), dim3(256), 0, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
+template <int W, int B>
+mx_status launch_rows2(const QuantRows2Args& a, int rnd, hipStream_t st) {
+    const int grid = grid_for(a.items, 256, 256 * 16);
+    if (rnd == MX_RNE)
+        hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RNE>), dim3(grid), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RTZ>), dim3(grid), dim3(256), 0, st, a);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
@@ -298,8 +386,8 @@ extern "C" size_t mx_mant_bytes(int64_t batch, int64_t rows, int64_t cols, mx_fo
 }
 
 extern "C" size_t mx_exps_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f) {
-    if (!format_ok_quant(f) || batch < 0 || rows < 0 || cols < 0) return 0;
-    return (size_t)(batch * rows * cols) / f.block;
+    if (!format_ok_quant(f) || batch < 0 || rows < 0 || cols < 0 || rows % f.block_rows != 0) return 0;
+    return (size_t)(batch * rows * cols) / (f.block * f.block_rows);
 }
 
 extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols,
@@ -309,6 +397,8 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
     if (batch < 0 || rows < 0 || cols < 0 || row_stride < cols) return MX_ERR_BAD_ARG;
     if (axis != 0 && axis != 1) return MX_ERR_BAD_ARG;
     if ((axis == 1 ? cols : rows) % f.block != 0) return MX_ERR_BAD_ARG;
+    if (f.block_rows == 2 && axis == 1 && rows % 2 != 0) return MX_ERR_BAD_ARG;
+    if (f.block_rows == 2 && axis == 0) return MX_ERR_UNSUPPORTED;
     if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!x || !mant || !exps) return MX_ERR_BAD_ARG;
@@ -316,7 +406,16 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
     hipStream_t st = (hipStream_t)stream;
     const int bias = (1 << (f.exp_bits - 1)) - 1;
     const int emax = ((1 << f.exp_bits) - 1) - bias;
-    if (axis == 1) {
+    if (axis == 1 && f.block_rows == 2) {
+        QuantRows2Args a;
+        a.x = x; a.mant = mant; a.exps = exps;
+        a.items = batch * (rows / 2) * (cols / 8);
+        a.row_octets = cols / 8;
+        a.pairs = rows / 2; a.row_stride = row_stride; a.batch_stride = batch_stride;
+        a.bias = bias; a.emax = emax;
+        a.vec = (((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0 && (batch_stride & 3) == 0) ? 1 : 0;
+        MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_rows2<kW, kB>(a, f.rounding, st))));
+    } else if (axis == 1) {
         QuantArgs a;
         a.x = x; a.mant = mant; a.exps = exps;
         a.octets = batch * rows * (cols / 8);
@@ -341,13 +440,15 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
 extern "C" mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows,
                                    int64_t cols, mx_format f, float* y, void* stream) {
     if (!format_ok_quant(f)) return MX_ERR_BAD_ARG;
-    if (batch < 0 || rows < 0 || cols < 0 || cols % f.block != 0) return MX_ERR_BAD_ARG;
+    if (batch < 0 || rows < 0 || cols < 0 || cols % f.block != 0 || rows % f.block_rows != 0) return MX_ERR_BAD_ARG;
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!mant || !exps || !y) return MX_ERR_BAD_ARG;
     if (((uintptr_t)y & 15) || ((uintptr_t)mant & 15)) return MX_ERR_BAD_ARG;
     DequantArgs a;
     a.mant = mant; a.exps = exps; a.y = y;
     a.octets = batch * rows * (cols / 8);
+    a.row_octets = cols / 8;
+    a.block_rows = f.block_rows;
     a.bias = (1 << (f.exp_bits - 1)) - 1;
     hipStream_t st = (hipStream_t)stream;
     MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_dequant<kW, kB>(a, st))));

@@ -26,17 +26,17 @@ EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "
 
 
 class mx_format(ctypes.Structure):
-    """Mirror of the C struct: block, exp_bits, mant_bits (stored bits incl. sign), rounding."""
+    """Mirror of the C struct: block, exp_bits, mant_bits (stored bits incl. sign), rounding, block_rows."""
     _fields_ = [("block", ctypes.c_int32), ("exp_bits", ctypes.c_int32),
-                ("mant_bits", ctypes.c_int32), ("rounding", ctypes.c_int32)]
+                ("mant_bits", ctypes.c_int32), ("rounding", ctypes.c_int32), ("block_rows", ctypes.c_int32)]
 
     def __repr__(self):
-        return "mx_format(block=%d, exp_bits=%d, mant_bits=%d, rounding=%d)" % (
-            self.block, self.exp_bits, self.mant_bits, self.rounding)
+        return "mx_format(block=%d, exp_bits=%d, mant_bits=%d, rounding=%d, block_rows=%d)" % (
+            self.block, self.exp_bits, self.mant_bits, self.rounding, self.block_rows)
 
 
-def fmt(block: int, mant_bits: int, exp_bits: int = 8, rounding: int = MX_RNE) -> mx_format:
-    return mx_format(block, exp_bits, mant_bits, rounding)
+def fmt(block: int, mant_bits: int, exp_bits: int = 8, rounding: int = MX_RNE, block_rows: int = 1) -> mx_format:
+    return mx_format(block, exp_bits, mant_bits, rounding, block_rows)
 
 
 class MxError(RuntimeError):

@@ -34,6 +34,10 @@ def test_size_accounting_matches_eq1(lib):
     f = mx.fmt(32, 8)
     n = 64 * 4096
     assert 8 * (mx.mx_mant_bytes(1, 64, 4096, f) + mx.mx_exps_bytes(1, 64, 4096, f)) / n == 8.25
+    # the paper's own shape: 16 columns x 2 rows per exponent, MXInt((16,2),8,7)
+    f2 = mx.fmt(16, 8, block_rows=2)
+    assert 8 * (mx.mx_mant_bytes(1, 64, 4096, f2) + mx.mx_exps_bytes(1, 64, 4096, f2)) / n == 8.25
+    assert mx.mx_exps_bytes(1, 63, 4096, f2) == 0                     # odd number of rows
     # the fragment layout keeps that density when no padding is needed (rows % 32 == 0, cols % (4*block) == 0)
     for block, w in [(16, 4), (32, 8), (16, 6), (64, 3)]:
         f = mx.fmt(block, w)
@@ -99,4 +103,4 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
 
 
 def test_struct_layout():
-    assert ctypes.sizeof(mx.mx_format) == 16
+    assert ctypes.sizeof(mx.mx_format) == 20

@@ -12,6 +12,7 @@ from oracle import mx_oracle as orc
 from paper_2307_15517_amd import inputs, mx
 
 pytestmark = pytest.mark.gpu
+MAT_LAYOUT = mx.MX_LAYOUT_MATRIX
 
 DEV = "cuda:0"
 TOL = 1e-5
@@ -158,6 +159,91 @@ def test_pack_unpack_roundtrip(block, w):
         m2, e2 = mx.unpack(packed, 2, rows, cols, f)
         torch.cuda.synchronize()
         assert np.array_equal(host(m2), mant) and np.array_equal(host(e2), exps)
+
+
+# ----------------------------------------------------------------------------------------------
+# Two-row blocks: the paper's block shape (block, 2), e.g. MXInt((16,2),8,7)
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("block", [8, 16, 32, 64])
+def test_quantize_two_row_blocks_bit_exact(block):
+    rng = np.random.default_rng(700 + block)
+    for w in range(2, 9):
+        f = mx.fmt(block, w, 8, mx.MX_RNE if w % 2 else mx.MX_RTZ, block_rows=2)
+        x = special_values(rng, 2 * 34, 3 * 64).reshape(2, 34, 3 * 64)
+        q, ex = zip(*(orc.quantize(x[b], block, w, 8, f.rounding, block_rows=2) for b in range(2)))
+        mant, exps = mx.quantize(dev(x), f)
+        torch.cuda.synchronize()
+        assert exps.numel() == 2 * 17 * (3 * 64 // block)
+        assert np.array_equal(host(exps), np.stack(ex).reshape(-1)), "exponent bytes differ"
+        assert np.array_equal(host(mant), np.stack([orc.pack_bits(qq, w) for qq in q]).reshape(-1)), "mantissa bytes differ"
+        # and back: the same values as the oracle's, both rows of a pair reading the pair's exponent
+        y = mx.dequantize(mant, exps, 2, 34, 3 * 64, f)
+        torch.cuda.synchronize()
+        ref = np.stack([orc.dequantize(q[b], orc.row_exps(ex[b], 2), block, w) for b in range(2)])
+        fine = np.abs(ref) >= 2.0 ** -126           # below that fp32 itself rounds
+        assert np.array_equal(host(y).astype(np.float64)[fine], ref[fine])
+    # strided rows
+    f = mx.fmt(block, 8, block_rows=2)
+    big = rng.standard_normal((20, 4 * 64 + 8)).astype(np.float32)
+    xd = dev(big)
+    mant = torch.empty(mx.mx_mant_bytes(1, 20, 4 * 64, f), dtype=torch.uint8, device=DEV)
+    exps = torch.empty(mx.mx_exps_bytes(1, 20, 4 * 64, f), dtype=torch.uint8, device=DEV)
+    mx.mx_quantize(xd, 1, 20, 4 * 64, 4 * 64 + 8, 0, 1, f, mant, exps)
+    q, ex = orc.quantize(big[:, :4 * 64], block, 8, block_rows=2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(mant), orc.pack_bits(q, 8).reshape(-1)) and np.array_equal(host(exps), ex.reshape(-1))
+
+
+@pytest.mark.parametrize("layout", [mx.MX_LAYOUT_FRAGMENT, mx.MX_LAYOUT_MATRIX])
+@pytest.mark.parametrize("block,w", [(16, 8), (16, 4), (16, 5), (32, 8), (32, 4), (64, 6)])
+def test_two_row_blocks_pack_roundtrip_and_fused(layout, block, w):
+    rng = np.random.default_rng(720 + block + w)
+    f = mx.fmt(block, w, block_rows=2)
+    for batch, rows, cols in [(1, 70, 5 * 64), (2, 34, 8 * 64), (1, 256, 1024)]:
+        x = (rng.standard_normal((batch, rows, cols)) * np.exp2(rng.integers(-6, 6, size=(batch, rows, 1)))).astype(np.float32)
+        xd = dev(x)
+        mant, exps = mx.quantize(xd, f)
+        n = mx.mx_packed_bytes(batch, rows, cols, f, layout)
+        packed = torch.zeros(n, dtype=torch.uint8, device=DEV)       # zeroed: the layouts leave their tail padding alone
+        fused = torch.zeros(n, dtype=torch.uint8, device=DEV)
+        mx.mx_pack(mant, exps, batch, rows, cols, f, layout, packed)
+        m2, e2 = mx.unpack(packed, batch, rows, cols, f, layout)
+        mx.mx_quantize_pack(xd, batch, rows, cols, cols, rows * cols, f, layout, fused)
+        torch.cuda.synchronize()
+        assert torch.equal(m2, mant) and torch.equal(e2, exps), "pack/unpack round trip"
+        assert torch.equal(fused, packed), "fused quantize+pack differs from quantize, then pack"
+
+
+def test_paper_type_linear_two_row_blocks():
+    """The paper's own types on a linear layer (Fig. 2b): activations MXInt((16,2),8,7), weights
+    MXInt((16,2),8,3), on both layouts; the product kernels see per-row exponents and do not change."""
+    case = inputs.opt125m_layer()[2]
+    x, wt = inputs.make(case)
+    fa, fb = mx.fmt(16, 8, block_rows=2), mx.fmt(16, 4, block_rows=2)
+    qa, ea = orc.quantize(x, 16, 8, block_rows=2)
+    qb, eb = orc.quantize(wt, 16, 4, block_rows=2)
+    y_ref, mag = orc.gemm(qa, orc.row_exps(ea, 2), 8, qb, orc.row_exps(eb, 2), 4, 16, want_mag=True)
+    for layout in (mx.MX_LAYOUT_FRAGMENT, MAT_LAYOUT):
+        A = mx.quantize_pack(dev(x), fa, layout)
+        B = mx.quantize_pack(dev(wt), fb, layout)
+        y = mx.gemm(A, fa, B, fb, case.M, case.N, case.K, layout=layout)
+        torch.cuda.synchronize()
+        say("two-row blocks, layout", layout, "worst", check_product(host(y)[0], y_ref, mag, "paper types"))
+
+
+def test_two_row_blocks_rejections():
+    f2 = mx.fmt(16, 8, block_rows=2)
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    xf = torch.zeros((8, 64), dtype=torch.float32, device=DEV)
+    out = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    assert mx.mx_quantize(xf, 1, 7, 64, 64, 0, 1, f2, buf, out, check=False) == mx.MX_ERR_BAD_ARG          # odd rows
+    assert mx.mx_quantize(xf, 1, 32, 16, 16, 0, 0, f2, buf, out, check=False) == mx.MX_ERR_UNSUPPORTED     # along the rows
+    assert mx.mx_cast(buf, buf, 1, 8, 64, f2, mx.fmt(16, 4, block_rows=2), out, out, check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_quantize(xf, 1, 8, 64, 64, 0, 1, mx.fmt(16, 8, block_rows=3), buf, out, check=False) == mx.MX_ERR_BAD_ARG
+    y = torch.zeros((2, 64), dtype=torch.float32, device=DEV)
+    assert mx.mx_linear(xf, 2, 64, 64, f2, buf, buf, 64, mx.fmt(16, 4), mx.MX_LAYOUT_FRAGMENT, y, 64,
+                        check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_exps_bytes(1, 8, 64, f2) == 4 * 4 and mx.mx_exps_bytes(1, 7, 64, f2) == 0
 
 
 # ----------------------------------------------------------------------------------------------
