@@ -85,7 +85,6 @@ struct DotArgs {
     // fused form (mx_linear): the left operand is still fp32 and is quantized on the way into LDS
     const float* x;      // null: take the packed left operand g.A
     int64_t x_stride;
-    int32_t x_vec;       // x and its stride allow 16-byte loads
     int32_t bias, emax, rounding;
 };
 
@@ -148,8 +147,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (m < g.M && e < g.K) {                           // K is a multiple of 4: all four or none
                 const float* src = a.x + (int64_t)m * a.x_stride + e;
-                if (a.x_vec) v = *reinterpret_cast<const float4*>(src);
-                else v = make_float4(src[0], src[1], src[2], src[3]);
+                v = *reinterpret_cast<const float4*>(src);       // the fused form is only entered with 16-byte aligned rows
             }
             return v;
         };
@@ -341,7 +339,7 @@ mx_status gemv_dot(const GemmArgs& g, int wa, int wb, int block, int64_t batch, 
     a.wa = wa;
     a.x = x;
     a.x_stride = x_stride;
-    a.x_vec = (x != nullptr && ((uintptr_t)x & 15) == 0 && (x_stride & 3) == 0) ? 1 : 0;
+    if (x != nullptr && (((uintptr_t)x & 15) != 0 || (x_stride & 3) != 0)) return MX_ERR_UNSUPPORTED;
     a.bias = a.emax = a.rounding = 0;
     if (x != nullptr) {
         a.bias = (1 << (fx->exp_bits - 1)) - 1;

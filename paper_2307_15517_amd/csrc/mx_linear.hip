@@ -28,7 +28,9 @@ struct LinQuantArgs {
 constexpr int kLqRowPitch = 256 + 16;     // bytes; the 16-byte skew spreads the lanes' rows over the banks
 constexpr int kLqTile = 32 * kLqRowPitch; // also holds the largest record (64 * 128 + 128 bytes)
 
-template <int W, int B, int RND>
+// VEC: 16-byte loads (x and its strides allow them).  A template parameter, not a run-time branch: with
+// both forms in one function the compiler folds them into the element-wise one.
+template <int W, int B, int RND, bool VEC>
 __global__ __launch_bounds__(256) void quantize_to_fragments_kernel(LinQuantArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * kLqTile];
     constexpr int kPieceDw = B * W / 16;          // dwords of one lane piece: four half blocks
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(256) void quantize_to_fragments_kernel(LinQuantArgs
             in[r] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (row < a.M && col < a.K) {
                 const float* src = xb + row * a.row_stride + col;
-                if (a.vec) in[r] = *reinterpret_cast<const float4*>(src);
+                if constexpr (VEC) in[r] = *reinterpret_cast<const float4*>(src);
                 else in[r] = make_float4(src[0], src[1], src[2], src[3]);
             }
         }
@@ -143,10 +145,13 @@ __global__ __launch_bounds__(256) void quantize_to_fragments_kernel(LinQuantArgs
 template <int W, int B>
 mx_status launch_lq(const LinQuantArgs& a, int64_t batch, int rnd, hipStream_t st) {
     dim3 grid((unsigned)(ceil_div(a.rows_out, 32) * ceil_div(a.chunks, 4)), (unsigned)batch);
-    if (rnd == MX_RNE)
-        hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RNE>), grid, dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RTZ>), grid, dim3(256), 0, st, a);
+    if (rnd == MX_RNE) {
+        if (a.vec) hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RNE, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RNE, false>), grid, dim3(256), 0, st, a);
+    } else {
+        if (a.vec) hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RTZ, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((quantize_to_fragments_kernel<W, B, MX_RTZ, false>), grid, dim3(256), 0, st, a);
+    }
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
@@ -209,7 +214,7 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
     if (K > 0 && (!x || !A_scratch || !B_packed)) return MX_ERR_BAD_ARG;
     if (((uintptr_t)x & 3) || ((uintptr_t)A_scratch & 255)) return MX_ERR_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if (K > 0 && M <= 2) {
+    if (K > 0 && M <= 2 && ((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0) {
         // one launch: the dot-product decode kernel quantizes the activations on its way into LDS
         // (same arithmetic, same accumulation order as the two-launch form); A_scratch is not touched
         const GemmArgs g = fragment_args(M, N, K, A_scratch, fx, B_packed, fb, Y, ldy, M * ldy);

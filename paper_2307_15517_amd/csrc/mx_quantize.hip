@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void quantize_axis1_kernel(QuantArgs a) {
 
 // Two-row blocks (the paper's block shape (B, 2), Section 4.1): rows 2p and 2p+1 share the exponents
 // of their blocks.  One lane owns the same 8 consecutive columns of both rows, LPB = B/8 adjacent
-// lanes own one block; items run with the columns fastest, so each row is read in whole segments.
+// lanes own one block; a workgroup takes 256 consecutive octets of one row pair.
 struct QuantRows2Args {
     const float* x;
     uint8_t* mant;
@@ -176,58 +176,65 @@ struct QuantRows2Args {
     int32_t bias;
     int32_t emax;
     int32_t vec;           // 16-byte loads are aligned
+    int32_t flat;          // the batch entries follow each other at rows * row_stride
+    int64_t chunks;        // workgroups per row pair: ceil(row_octets / 256)
 };
 
-template <int W, int B, int RND>
+// VEC: 16-byte loads.  A template parameter, not a run-time branch: with both forms in one function
+// the compiler folds them into the element-wise one.
+template <int W, int B, int RND, bool VEC>
 __global__ __launch_bounds__(256) void quantize_rows2_kernel(QuantRows2Args a) {
     constexpr int LPB = B / 8;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    const int64_t first = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t wave_first = first - (threadIdx.x & 63);
-    for (int64_t wo = wave_first, o = first; wo < a.items; wo += stride, o += stride) {
-        const bool live = o < a.items;
-        const int64_t pr = o / a.row_octets, c8 = o - pr * a.row_octets;      // pair index over the batch, octet
+    // one workgroup per (row pair, run of 256 octets): no per-item index arithmetic
+    const int64_t pr = blockIdx.x / a.chunks;                       // pair index over the batch (scalar)
+    const int64_t c8 = (blockIdx.x - pr * a.chunks) * 256 + threadIdx.x;
+    const bool live = c8 < a.row_octets;                            // whole blocks: row_octets is a multiple of LPB
+    const float* pair0;                                             // first row of the pair
+    if (a.flat) {
+        pair0 = a.x + 2 * pr * a.row_stride;
+    } else {
         const int64_t b = pr / a.pairs, p = pr - b * a.pairs;
-        float v[2][8];
+        pair0 = a.x + b * a.batch_stride + 2 * p * a.row_stride;
+    }
+    float v[2][8];
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            if (live) {
-                const float* src = a.x + b * a.batch_stride + (2 * p + r) * a.row_stride + c8 * 8;
-                if (a.vec) {
-                    const float4 lo = reinterpret_cast<const float4*>(src)[0];
-                    const float4 hi = reinterpret_cast<const float4*>(src)[1];
-                    v[r][0] = lo.x; v[r][1] = lo.y; v[r][2] = lo.z; v[r][3] = lo.w;
-                    v[r][4] = hi.x; v[r][5] = hi.y; v[r][6] = hi.z; v[r][7] = hi.w;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) v[r][i] = src[i];
-                }
+    for (int r = 0; r < 2; ++r) {
+        if (live) {
+            const float* src = pair0 + r * a.row_stride + c8 * 8;
+            if constexpr (VEC) {
+                const float4 lo = reinterpret_cast<const float4*>(src)[0];
+                const float4 hi = reinterpret_cast<const float4*>(src)[1];
+                v[r][0] = lo.x; v[r][1] = lo.y; v[r][2] = lo.z; v[r][3] = lo.w;
+                v[r][4] = hi.x; v[r][5] = hi.y; v[r][6] = hi.z; v[r][7] = hi.w;
             } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v[r][i] = 0.f;
+                for (int i = 0; i < 8; ++i) v[r][i] = src[i];
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[r][i] = 0.f;
         }
-        uint32_t am = 0;
+    }
+    uint32_t am = 0;
 #pragma unroll
-        for (int r = 0; r < 2; ++r)
+    for (int r = 0; r < 2; ++r)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t ab = __float_as_uint(v[r][i]) & 0x7fffffffu;
-                am = ab > am ? ab : am;
-            }
-        am = group_max_u32<LPB>(am);
-        const int E = block_exponent(am, a.bias, a.emax);
-        const int shift = (W - 2) - E;
-        if (live) {
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                int q[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(v[r][i], shift);
-                store_stream<W>(a.mant + ((pr * 2 + r) * a.row_octets + c8) * W, pack8<W>(q));
-            }
-            if ((threadIdx.x & (LPB - 1)) == 0) a.exps[o / LPB] = (uint8_t)(E + a.bias);
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t ab = __float_as_uint(v[r][i]) & 0x7fffffffu;
+            am = ab > am ? ab : am;
         }
+    am = group_max_u32<LPB>(am);
+    const int E = block_exponent(am, a.bias, a.emax);
+    const int shift = (W - 2) - E;
+    if (live) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            int q[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(v[r][i], shift);
+            store_stream<W>(a.mant + ((pr * 2 + r) * a.row_octets + c8) * W, pack8<W>(q));
+        }
+        if ((threadIdx.x & (LPB - 1)) == 0) a.exps[(pr * a.row_octets + c8) / LPB] = (uint8_t)(E + a.bias);
     }
 }
 
@@ -326,11 +333,16 @@ mx_status launch_axis1(const QuantArgs& a, int rnd, hipStream_t st) {
 
 template <int W, int B>
 mx_status launch_rows2(const QuantRows2Args& a, int rnd, hipStream_t st) {
-    const int grid = grid_for(a.items, 256, 256 * 16);
-    if (rnd == MX_RNE)
-        hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RNE>), dim3(grid), dim3(256), 0, st, a);
-    else
-        hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RTZ>), dim3(grid), dim3(256), 0, st, a);
+    const int64_t wgs = a.items / a.row_octets * a.chunks;
+    if (wgs > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)wgs);
+    if (rnd == MX_RNE) {
+        if (a.vec) hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RNE, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RNE, false>), grid, dim3(256), 0, st, a);
+    } else {
+        if (a.vec) hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RTZ, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((quantize_rows2_kernel<W, B, MX_RTZ, false>), grid, dim3(256), 0, st, a);
+    }
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
@@ -414,6 +426,8 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
         a.pairs = rows / 2; a.row_stride = row_stride; a.batch_stride = batch_stride;
         a.bias = bias; a.emax = emax;
         a.vec = (((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0 && (batch_stride & 3) == 0) ? 1 : 0;
+        a.chunks = ceil_div(a.row_octets, 256);
+        a.flat = (batch == 1 || batch_stride == rows * row_stride) ? 1 : 0;
         MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_rows2<kW, kB>(a, f.rounding, st))));
     } else if (axis == 1) {
         QuantArgs a;
