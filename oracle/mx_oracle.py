@@ -205,3 +205,23 @@ def linear(x: np.ndarray, wt: np.ndarray, block: int, wx: int, ww: int, e: int =
     qa, ea = quantize(x, block, wx, e, rounding)
     qb, eb = quantize(wt, block, ww, e, rounding)
     return gemm(qa, ea, wx, qb, eb, ww, block, e, want_mag=want_mag)
+
+
+def linear_q(x: np.ndarray, wt: np.ndarray, bias: Optional[np.ndarray], block: int, wx: int, ww: int, wbias: int,
+             wo: int, e: int = 8, rounding: int = RNE, block_rows: int = 1):
+    """The emulated linear layer of Section 3.2 in full (the LinearOp of Fig. 2b): quantize x [M,K], the
+    weights wt [N,K] and the bias [N] to MXInt, take the MXInt product, add the bias, and quantize the
+    result (held in fp32, the emulator's working precision) to the output format, blocks along N.
+
+    Returns (q_out int8 [M,N], exps_out uint8 [M/block_rows, N/block], y float64 [M,N] before the output
+    quantizer, mag float64 [M,N] = sum_b |term_b| + |bias|)."""
+    qa, ea = quantize(x, block, wx, e, rounding, block_rows=block_rows)
+    qb, eb = quantize(wt, block, ww, e, rounding, block_rows=block_rows)
+    y, mag = gemm(qa, row_exps(ea, block_rows), wx, qb, row_exps(eb, block_rows), ww, block, e, want_mag=True)
+    if bias is not None:
+        bq, be = quantize(np.asarray(bias, np.float32).reshape(1, -1), block, wbias, e, rounding)
+        bv = dequantize(bq, be, block, wbias, e)
+        y = y + bv
+        mag = mag + np.abs(bv)
+    qo, eo = quantize(y.astype(np.float32), block, wo, e, rounding, block_rows=block_rows)
+    return qo, eo, y, mag

@@ -487,3 +487,34 @@ def test_cast_invariants():
             err = np.abs(orc.dequantize(nq, ne, block, wd) - orc.dequantize(q8, e8, block, 8))
             sat = np.abs(nq) == 2 ** (wd - 1) - 1
             assert np.all(err[~sat] <= lim * unit[~sat]) and np.all(err[sat] <= unit[sat])
+
+
+# ----------------------------------------------------------------------------------------------
+# The emulated linear layer with bias and output quantizer (Section 3.2; the LinearOp of Fig. 2b)
+# ----------------------------------------------------------------------------------------------
+def test_linear_q_hand_worked_and_composition():
+    # x = [1, 0.5 | 0.25, 0.25], W row 0 = [1, 1 | 2, -2], row 1 = [0.5, 0 | 0, 1]; blocks of 2; 8-bit everything:
+    # every value is exact in its block, so y = [1.5 + 0, 0.5 + 0.25] = [1.5, 0.75]; bias [0.25, -0.75] -> [1.75, 0.0]
+    x = np.array([[1.0, 0.5, 0.25, 0.25]], np.float32)
+    wt = np.array([[1.0, 1.0, 2.0, -2.0], [0.5, 0.0, 0.0, 1.0]], np.float32)
+    bias = np.array([0.25, -0.75], np.float32)
+    qo, eo, y, mag = orc.linear_q(x, wt, bias, 2, 8, 8, 8, 4)
+    assert y.tolist() == [[1.75, 0.0]]
+    # output block [1.75, 0]: E = 0 (byte 127), 4 bits: unit 0.25 -> q = [7, 0]
+    assert qo.tolist() == [[7, 0]] and eo.tolist() == [[127]]
+    assert mag.tolist() == [[1.5 + 0.0 + 0.25, 0.5 + 0.25 + 0.75]]      # |block sums| + |bias|
+    # composition: the same as the separately pinned pieces
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((6, 64)).astype(np.float32)
+    wt = (rng.standard_normal((32, 64)) * 0.1).astype(np.float32)
+    b = rng.standard_normal(32).astype(np.float32)
+    for br in (1, 2):
+        qo, eo, y, _ = orc.linear_q(x, wt, b, 16, 8, 4, 4, 6, block_rows=br)
+        qa, ea = orc.quantize(x, 16, 8, block_rows=br)
+        qb, eb = orc.quantize(wt, 16, 4, block_rows=br)
+        ref = orc.dequantize(qa, orc.row_exps(ea, br), 16, 8) @ orc.dequantize(qb, orc.row_exps(eb, br), 16, 4).T
+        bq, be = orc.quantize(b.reshape(1, -1), 16, 4)
+        ref = ref + orc.dequantize(bq, be, 16, 4)
+        assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+        q2, e2 = orc.quantize(y.astype(np.float32), 16, 6, block_rows=br)
+        assert np.array_equal(qo, q2) and np.array_equal(eo, e2)
