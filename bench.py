@@ -216,6 +216,29 @@ def main():
             "GBps": round(cbytes / ms / 1e6, 1), "frac_hbm": round(cbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
             "us": round(ms * 1e3, 2), "bytes": int(cbytes)}
         del m8s, calls
+        # the whole emulated linear layer (product + MXInt bias + output quantizer) in one kernel, against the
+        # same three steps one after the other; block 16 (the paper's block length), 8-bit in and out, 4-bit weights
+        c = work[0]["case"]
+        fa16, fb16, fo16, fbias16 = mx.fmt(16, 8), mx.fmt(16, 4), mx.fmt(16, 8), mx.fmt(16, 4)
+        x16 = work[0]["xs"][0]
+        w16 = torch.randn((c.N, c.K), dtype=torch.float32, device=dev) * 0.02
+        A16 = mx.quantize_pack(x16, fa16, L)
+        B16 = mx.quantize_pack(w16, fb16, L)
+        bm16, be16 = mx.quantize(torch.randn((1, c.N), dtype=torch.float32, device=dev), fbias16)
+        o16 = torch.empty(mx.mx_packed_bytes(1, c.M, c.N, fo16, L), dtype=torch.uint8, device=dev)
+        y16 = torch.empty((c.M, c.N), dtype=torch.float32, device=dev)
+        if args.layout == "matrix":
+            fused = mx.bound("mx_gemm_q", 1, c.M, c.N, c.K, A16, fa16, B16, fb16, L, bm16, be16, fbias16, fo16, o16)
+            plain = mx.bound("mx_gemm", 1, c.M, c.N, c.K, A16, fa16, B16, fb16, L, y16, c.N, 0)
+            requant = mx.bound("mx_quantize_pack", y16, 1, c.M, c.N, c.N, 0, fo16, L, o16)
+            ops16 = 2.0 * c.M * c.N * c.K
+            ms_f = time_launches(lambda i: fused(), 20)
+            ms_p = time_launches(lambda i: plain(), 20)
+            ms_pq = time_launches(lambda i: (plain(), requant()), 20)
+            kernels["gemm_q_%dx%dx%d_b16_fused" % (c.M, c.N, c.K)] = {"us": round(ms_f * 1e3, 2), "TOPS": round(ops16 / ms_f / 1e9, 1)}
+            kernels["gemm_%dx%dx%d_b16" % (c.M, c.N, c.K)] = {"us": round(ms_p * 1e3, 2), "TOPS": round(ops16 / ms_p / 1e9, 1)}
+            kernels["gemm_then_quantize_pack_%dx%dx%d_b16" % (c.M, c.N, c.K)] = {"us": round(ms_pq * 1e3, 2), "TOPS": round(ops16 / ms_pq / 1e9, 1)}
+        del A16, B16, o16, y16, w16
         # decode linear, LLaMA-13B shapes: 0.5625*N*K + 4*M*K + 4*M*N bytes per call
         for M in (1, 4, 8):
             for dc in inputs.llama13b_decode(M):

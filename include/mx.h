@@ -191,6 +191,22 @@ MX_API mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const v
                   int64_t batch_stride_y, void* stream);
 
 /*
+ * The emulated operator in full (Section 3.2: quantize the inputs, the operator, quantize the result;
+ * Fig. 2b: a linear layer whose bias is MXInt as well): the product of mx_gemm, plus an optional
+ * bias, quantized to format `fo` with blocks along N (the axis the next layer reduces over), without
+ * the fp32 result going through memory:
+ *     out = mx_quantize_pack( fp32(A x B^T) + fp32(bias), fo, layout )       [batch x M x N]
+ * bias_mant / bias_exps: canonical form of one row of N elements in format fbias (block_rows 1, same
+ * block as fo), shared by the batch; both null for no bias.  The fp32 sum is rounded once more by the
+ * addition; the quantizer arithmetic is that of mx_quantize.  out_packed: mx_packed_bytes(batch, M, N,
+ * fo, layout) bytes, 256-byte aligned.  MX_ERR_UNSUPPORTED unless layout is MX_LAYOUT_MATRIX and the
+ * blocks of fa, fb and fo are 16 (the bfloat16 form); M must be a multiple of fo.block_rows.
+ */
+MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed, mx_format fa,
+                    const void* B_packed, mx_format fb, int32_t layout, const uint8_t* bias_mant,
+                    const uint8_t* bias_exps, mx_format fbias, mx_format fo, void* out_packed, void* stream);
+
+/*
  * Linear layer on fp32 activations for decode (M <= 8): quantizes x [M x K] with fx
  * on the fly (same arithmetic as mx_quantize, axis 1), then the product above
  * against B_packed [N x K].  The result equals mx_quantize + mx_pack + mx_gemm.

@@ -7,6 +7,9 @@ mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void
                       mx_format fb, float* Y, int64_t ldy, int64_t batch_stride_y, hipStream_t st);
 mx_status gemm_bf16(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, const void* B, float* Y,
                     int64_t ldy, int64_t batch_stride_y, hipStream_t st);
+mx_status gemm_bf16_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+                      const uint8_t* bias_mant, const uint8_t* bias_exps, mx_format fbias, mx_format fo, void* out,
+                      hipStream_t st);
 }  // namespace mx
 
 namespace mx {
@@ -61,4 +64,27 @@ extern "C" mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, con
         case 64: return gemm_block64(g, fa.mant_bits, fb.mant_bits, batch, st);
     }
     return MX_ERR_UNSUPPORTED;
+}
+
+extern "C" mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed, mx_format fa,
+                               const void* B_packed, mx_format fb, int32_t layout, const uint8_t* bias_mant,
+                               const uint8_t* bias_exps, mx_format fbias, mx_format fo, void* out_packed,
+                               void* stream) {
+    if (!format_ok_quant(fa) || !format_ok_quant(fb) || !format_ok_quant(fo)) return MX_ERR_BAD_ARG;
+    if (fa.block != fb.block || fa.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
+    const bool with_bias = bias_mant != nullptr || bias_exps != nullptr;
+    if (with_bias && (!bias_mant || !bias_exps || !format_ok_quant(fbias) || fbias.block != fo.block ||
+                      fbias.block_rows != 1)) return MX_ERR_BAD_ARG;
+    if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
+    if (batch < 0 || M < 0 || N < 0 || K < 0 || K % fa.block != 0 || N % fo.block != 0 || M % fo.block_rows != 0)
+        return MX_ERR_BAD_ARG;
+    // built for the block-16 form of the matrix layout on both sides
+    if (layout != MX_LAYOUT_MATRIX || fa.block != 16 || fo.block != 16) return MX_ERR_UNSUPPORTED;
+    if (batch == 0 || M == 0 || N == 0) return MX_OK;
+    if (!out_packed || ((uintptr_t)out_packed & 255)) return MX_ERR_BAD_ARG;
+    if (K > 0 && (!A_packed || !B_packed)) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)A_packed & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
+    if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    return gemm_bf16_q(batch, M, N, K, A_packed, B_packed, bias_mant, bias_exps, fbias, fo, out_packed,
+                       (hipStream_t)stream);
 }

@@ -34,6 +34,13 @@ struct BfArgs {
     int64_t matrixA, matrixB;
     int64_t ldy, batch_stride_y;
     int32_t tiles_m, tiles_n;      // workgroup tiles along M and N
+    // quantized output (mx_gemm_q): the result leaves as a packed block-16 operand [M x N], blocks along N
+    uint8_t* out;
+    BfGeom go;
+    const uint8_t* bias_mant;      // canonical MXInt bias [N] (one row), or null
+    const uint8_t* bias_exps;
+    int32_t wbias, bias_b;         // stored width and exponent bias of the bias format
+    int32_t wo, bias_o, emax_o, rnd_o, brows_o;   // output format
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_addr + 16*L.
@@ -60,7 +67,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // S: LDS stages.  The stage of step ks is free once its fragments are in registers, i.e. from the
 // barrier of step ks on, so the copy of step ks+S is issued during step ks.
 // OCC: workgroups the register and LDS budget must leave room for on one compute unit.
-template <int TM, int TN, int S, int OCC>
+// QOUT: instead of storing fp32, add the bias and quantize the tile to the output format
+// (Section 3.2 of the paper: the emulated operator quantizes its result; Fig. 2b: the linear layer's
+// bias is MXInt too), writing the packed operand the next product reads.
+template <int TM, int TN, int S, int OCC, bool QOUT>
 __global__ __launch_bounds__(256, OCC) void gemm_bf16_kernel(BfArgs g) {
     constexpr int UA = 2 * TM, UB = 2 * TN;            // units (row tiles) of the A / B tile per K step
     constexpr int NU = UA + UB;
@@ -191,8 +201,95 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_kernel(BfArgs g) {
     wait_vmcnt<0>();                                      // the clamped tail copies must not outlive the LDS
 
     const int64_t rtA0 = (bm * 2 + wm) * RA, rtB0 = (bn * 2 + wn) * RB;
-    float* Y = g.Y + bz * g.batch_stride_y;
     const int i = lane & 31, h = lane >> 5;
+    if constexpr (QOUT) {
+        // One row tile of the wave at a time: accumulators -> the wave's LDS tile, row-major; then lane
+        // 32*h' + i' holds half h' of each 16-element block of row i' (what the layout's fragments hold),
+        // completes the block maximum with its partner lane, quantizes and stores 16 bytes per fragment.
+        constexpr int PITCH = 32 * RB + 4;               // floats; the skew spreads the rows over the banks
+        static_assert(4 * 32 * PITCH * 4 + 64 * TN * 4 <= S * STAGE, "the turn-around tiles and the bias fit in the stages");
+        __syncthreads();                                 // every wave is done reading the stages
+        float* tile = reinterpret_cast<float*>(smem) + wave * (32 * PITCH);
+        // the bias of the workgroup's columns, decoded once
+        float* bias_lds = reinterpret_cast<float*>(smem) + 4 * 32 * PITCH;
+        if (g.bias_mant != nullptr) {
+            for (int c = threadIdx.x; c < 64 * TN; c += 256) {
+                const int64_t n = bn * (64 * TN) + c;
+                float bv = 0.f;
+                if (n < g.N) {
+                    const int64_t bit = n * g.wbias;
+                    const int sh = (int)(bit & 7);
+                    uint32_t code = g.bias_mant[bit >> 3];
+                    if (sh + g.wbias > 8) code |= (uint32_t)g.bias_mant[(bit >> 3) + 1] << 8;
+                    const int q = ((int)((code >> sh) << (32 - g.wbias))) >> (32 - g.wbias);
+                    bv = __builtin_ldexpf((float)q, (int)g.bias_exps[n >> 4] - g.bias_b - (g.wbias - 2));
+                }
+                bias_lds[c] = bv;
+            }
+            __syncthreads();
+        }
+        uint8_t* obase = g.out + bz * g.go.matrix;
+        const float qmax = (float)((1 << (g.wo - 1)) - 1);
+#pragma unroll
+        for (int ta = 0; ta < RA; ++ta) {
+#pragma unroll
+            for (int tb = 0; tb < RB; ++tb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) tile[(8 * (r >> 2) + 4 * h + (r & 3)) * PITCH + tb * 32 + i] = acc[ta][tb][r];
+            __builtin_amdgcn_wave_barrier();
+            const int64_t rt = rtA0 + ta, row = rt * 32 + i;
+#pragma unroll
+            for (int f = 0; f < 2 * RB; ++f) {
+                const int64_t kf = rtB0 * 2 + f;          // block along N
+                const int64_t col0 = kf * 16 + h * 8;
+                const bool inside = row < g.M && col0 < g.N;
+                const float4 t0 = *reinterpret_cast<const float4*>(tile + i * PITCH + f * 16 + h * 8);
+                const float4 t1 = *reinterpret_cast<const float4*>(tile + i * PITCH + f * 16 + h * 8 + 4);
+                float v[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+                if (!inside) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[e] = 0.f;
+                } else if (g.bias_mant != nullptr) {
+                    const float4 b0 = *reinterpret_cast<const float4*>(bias_lds + wn * (32 * RB) + f * 16 + h * 8);
+                    const float4 b1 = *reinterpret_cast<const float4*>(bias_lds + wn * (32 * RB) + f * 16 + h * 8 + 4);
+                    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+                    v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+                }
+                uint32_t am = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t ab = __float_as_uint(v[e]) & 0x7fffffffu;
+                    am = ab > am ? ab : am;
+                }
+                const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
+                am = o > am ? o : am;
+                if (g.brows_o == 2) {                     // two-row blocks: the neighbouring lane holds the other row
+                    const uint32_t o2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);
+                    am = o2 > am ? o2 : am;
+                }
+                const int ef = (int)(am >> 23);
+                int E = ef == 0 ? -127 : ef - 127;
+                E = E < -g.bias_o ? -g.bias_o : E;
+                E = E > g.emax_o ? g.emax_o : E;
+                uint32_t out[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float sc = __builtin_ldexpf(v[e], (g.wo - 2) - E);
+                    float r = g.rnd_o == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
+                    r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+                    r += 0.0f;                           // -0.0 -> +0.0
+                    out[e >> 1] |= bf16_of(r, E - (g.wo - 2)) << (16 * (e & 1));
+                }
+                if (rt < g.go.row_tiles && kf < g.go.ksteps * 2)
+                    *reinterpret_cast<uint4*>(obase + bf_frag(g.go, rt, kf >> 1, (int)(kf & 1), lane)) =
+                        make_uint4(out[0], out[1], out[2], out[3]);
+                if (h == 0 && row < g.M && kf < g.go.nblk) obase[g.go.frag_bytes + row * g.go.nblk + kf] = (uint8_t)(E + g.bias_o);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+    float* Y = g.Y + bz * g.batch_stride_y;
 #pragma unroll
     for (int ta = 0; ta < RA; ++ta) {
 #pragma unroll
@@ -207,11 +304,11 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_kernel(BfArgs g) {
     }
 }
 
-template <int TM, int TN, int S, int OCC>
+template <int TM, int TN, int S, int OCC, bool QOUT>
 mx_status launch_bf16(BfArgs& g, int64_t batch, hipStream_t st) {
     constexpr int smem = S * (2 * TM + 2 * TN) * kBfUnitBytes;
     static_assert(smem * OCC <= 160 * 1024, "LDS budget of one compute unit");
-    auto kern = gemm_bf16_kernel<TM, TN, S, OCC>;
+    auto kern = gemm_bf16_kernel<TM, TN, S, OCC, QOUT>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -241,9 +338,32 @@ mx_status gemm_bf16(int64_t batch, int64_t M, int64_t N, int64_t K, const void* 
     g.tilesA = ga.row_tiles; g.tilesB = gb.row_tiles; g.ksteps = ga.ksteps;
     g.matrixA = ga.matrix; g.matrixB = gb.matrix; g.ldy = ldy; g.batch_stride_y = batch_stride_y;
     g.tiles_m = g.tiles_n = 0;
+    g.out = nullptr; g.bias_mant = g.bias_exps = nullptr;
     const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 256) * batch;
-    if (tiles >= 2 * 256) return launch_bf16<2, 4, 3, 2>(g, batch, st);
-    return launch_bf16<2, 4, 4, 1>(g, batch, st);
+    if (tiles >= 2 * 256) return launch_bf16<2, 4, 3, 2, false>(g, batch, st);
+    return launch_bf16<2, 4, 4, 1, false>(g, batch, st);
+}
+
+// The same product with the bias added and the result quantized to `fo` (block 16, blocks along N),
+// written as the packed operand [M x N] of the matrix layout.
+mx_status gemm_bf16_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+                      const uint8_t* bias_mant, const uint8_t* bias_exps, mx_format fbias, mx_format fo, void* out,
+                      hipStream_t st) {
+    const BfGeom ga = bf_geom(M, K), gb = bf_geom(N, K);
+    BfArgs g;
+    g.A = (const uint8_t*)A; g.B = (const uint8_t*)B; g.Y = nullptr; g.M = M; g.N = N;
+    g.tilesA = ga.row_tiles; g.tilesB = gb.row_tiles; g.ksteps = ga.ksteps;
+    g.matrixA = ga.matrix; g.matrixB = gb.matrix; g.ldy = 0; g.batch_stride_y = 0;
+    g.tiles_m = g.tiles_n = 0;
+    g.out = (uint8_t*)out; g.go = bf_geom(M, N);
+    g.bias_mant = bias_mant; g.bias_exps = bias_exps;
+    g.wbias = fbias.mant_bits; g.bias_b = (1 << (fbias.exp_bits - 1)) - 1;
+    g.wo = fo.mant_bits; g.bias_o = (1 << (fo.exp_bits - 1)) - 1;
+    g.emax_o = ((1 << fo.exp_bits) - 1) - g.bias_o;
+    g.rnd_o = fo.rounding; g.brows_o = fo.block_rows;
+    const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 256) * batch;
+    if (tiles >= 2 * 256) return launch_bf16<2, 4, 3, 2, true>(g, batch, st);
+    return launch_bf16<2, 4, 4, 1, true>(g, batch, st);
 }
 
 }  // namespace mx

@@ -22,7 +22,7 @@ MX_LAYOUT_MATRIX = 1
 
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
            "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
-           "mx_linear")
+           "mx_gemm_q", "mx_linear")
 
 
 class mx_format(ctypes.Structure):
@@ -70,9 +70,10 @@ def load() -> ctypes.CDLL:
     lib.mx_quantize_pack.argtypes = [vp, i64, i64, i64, i64, i64, mx_format, i32, vp, vp]
     lib.mx_unpack.argtypes = [vp, i64, i64, i64, mx_format, i32, vp, vp, vp]
     lib.mx_gemm.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, i64, i64, vp]
+    lib.mx_gemm_q.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, vp, mx_format, mx_format, vp, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
     for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
-                 "mx_linear"):
+                 "mx_gemm_q", "mx_linear"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -172,6 +173,15 @@ def mx_gemm(batch, M, N, K, A_packed, fa, B_packed, fb, layout, Y, ldy, batch_st
                        batch_stride_y, _stream(stream))
     if check:
         _raise(s, "mx_gemm")
+    return s
+
+
+def mx_gemm_q(batch, M, N, K, A_packed, fa, B_packed, fb, layout, bias_mant, bias_exps, fbias, fo, out_packed,
+              stream=None, check: bool = True) -> int:
+    s = load().mx_gemm_q(batch, M, N, K, _p(A_packed), fa, _p(B_packed), fb, layout, _p(bias_mant), _p(bias_exps),
+                         fbias, fo, _p(out_packed), _stream(stream))
+    if check:
+        _raise(s, "mx_gemm_q")
     return s
 
 

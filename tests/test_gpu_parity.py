@@ -764,6 +764,81 @@ def test_matrix_attention_full_size_sampled_heads_and_rows():
         say("output head", hd, "worst", check_product(host(O[hd, r0:r1]), o_ref[r0:r1], o_mag[r0:r1], "output"))
 
 
+def check_quantized_output(q_g, e_g, q_o, e_o, y, mag, block, w, block_rows):
+    """The fused output quantizer decides integers from fp32 sums that differ from the oracle's within the
+    product tolerance, so codes may differ where a value sits on a rounding or binade boundary.  Checked:
+    (1) every block exponent is the binade of a block maximum within the tolerance; (2) every mantissa is a
+    correct rounding (or saturation) of a value within the tolerance; (3) all but a sliver equal the oracle's."""
+    tol = TOL * mag + 2.0 ** -22 * np.abs(y) + F32_TINY
+    M, N = y.shape
+    nb = N // block
+    qmax = 2 ** (w - 1) - 1
+    Eg = orc.row_exps(e_g, block_rows).astype(np.int64) - 127                          # [M, nb]
+    blk = lambda a: a.reshape(M // block_rows, block_rows, nb, block).transpose(0, 2, 1, 3).reshape(M // block_rows, nb, -1)
+    hi = blk(np.abs(y) + tol).max(axis=2)
+    lo = np.maximum(blk(np.abs(y) - tol), 0).max(axis=2)
+    Eb = e_g.astype(np.int64) - 127                                                    # [M/R, nb]
+    zero = e_g == 0
+    assert np.all(hi[zero] < 2.0 ** -126), "zero exponent byte on a block that is not (nearly) zero"
+    nz = ~zero
+    assert np.all(np.ldexp(1.0, Eb[nz]) <= hi[nz]) and np.all(lo[nz] < np.ldexp(2.0, Eb[nz])), "block exponent off"
+    unit = np.repeat(np.ldexp(1.0, Eg - (w - 2)), block, axis=1)
+    xhat = q_g.astype(np.float64) * unit
+    near = np.abs(xhat - y) <= 0.5 * unit + tol
+    sat = (np.abs(q_g) == qmax) & (np.abs(y) >= (qmax - 0.5) * unit - tol)
+    assert np.all(near | sat), "a mantissa is not a rounding of the value: worst %g units" % float(
+        (np.abs(xhat - y) / unit)[~(near | sat)].max())
+    same = np.mean((q_g == q_o) & np.repeat(orc.row_exps(e_g == e_o, block_rows), block, axis=1))
+    assert same >= 0.999, "only %.4f of the codes equal the oracle's" % same
+    return float(same)
+
+
+@pytest.mark.parametrize("block_rows,wo", [(1, 8), (1, 4), (2, 8), (2, 5)])
+def test_gemm_q_bias_and_output_quantizer(block_rows, wo):
+    """mx_gemm_q: product + MXInt bias + output quantizer in one kernel, against the oracle's emulated
+    linear layer, and bit for bit against mx_gemm, the fp32 bias add and mx_quantize_pack run one by one."""
+    rng = np.random.default_rng(40 + wo + block_rows)
+    block, wx, ww, wbias = 16, 8, 4, 4
+    for M, K, N in [(128, 768, 3072), (70, 7 * 16, 16 * 11)]:
+        x = rng.standard_normal((M, K)).astype(np.float32)
+        wt = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+        bias = (rng.standard_normal(N) * 0.1).astype(np.float32)
+        fa, fb = mx.fmt(block, wx, block_rows=block_rows), mx.fmt(block, ww, block_rows=block_rows)
+        fbias, fo = mx.fmt(block, wbias), mx.fmt(block, wo, block_rows=block_rows)
+        A = mx.quantize_pack(dev(x), fa, MAT)
+        B = mx.quantize_pack(dev(wt), fb, MAT)
+        bm, be = mx.quantize(dev(bias.reshape(1, N)), fbias)
+        n_out = mx.mx_packed_bytes(1, M, N, fo, MAT)
+        out = torch.zeros(n_out, dtype=torch.uint8, device=DEV)
+        mx.mx_gemm_q(1, M, N, K, A, fa, B, fb, MAT, bm, be, fbias, fo, out)
+        # the same, one kernel after the other
+        y = mx.gemm(A, fa, B, fb, M, N, K, layout=MAT)[0]
+        yb = y + mx.dequantize(bm, be, 1, 1, N, fbias)[0]
+        ref = torch.zeros(n_out, dtype=torch.uint8, device=DEV)
+        mx.mx_quantize_pack(yb.contiguous(), 1, M, N, N, 0, fo, MAT, ref)
+        out2 = torch.zeros(n_out, dtype=torch.uint8, device=DEV)
+        mx.mx_gemm_q(1, M, N, K, A, fa, B, fb, MAT, None, None, fbias, fo, out2)          # no bias
+        ref2 = torch.zeros(n_out, dtype=torch.uint8, device=DEV)
+        mx.mx_quantize_pack(y.contiguous(), 1, M, N, N, 0, fo, MAT, ref2)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), "fused output differs from gemm, bias add, quantize+pack"
+        assert torch.equal(out2, ref2), "fused output without bias differs from gemm, quantize+pack"
+        # against the oracle
+        q_o, e_o, y_ref, mag = orc.linear_q(x, wt, bias, block, wx, ww, wbias, wo, block_rows=block_rows)
+        mg, eg = mx.unpack(out, 1, M, N, fo, MAT)
+        torch.cuda.synchronize()
+        q_g = orc.unpack_bits(host(mg).reshape(M, -1), N, wo)
+        e_g = host(eg).reshape(M // block_rows, N // block)
+        say("gemm_q", (M, K, N), "codes equal to the oracle's:", check_quantized_output(
+            q_g, e_g, q_o, e_o, y_ref, mag, block, wo, block_rows))
+    f16, f32_ = mx.fmt(16, 8), mx.fmt(32, 8)
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    assert mx.mx_gemm_q(1, 32, 64, 64, buf, f32_, buf, f32_, MAT, None, None, f32_, f32_, buf, check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_gemm_q(1, 32, 64, 64, buf, f16, buf, f16, mx.MX_LAYOUT_FRAGMENT, None, None, f16, f16, buf, check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_gemm_q(1, 32, 72, 64, buf, f16, buf, f16, MAT, None, None, f16, f16, buf, check=False) == mx.MX_ERR_BAD_ARG
+    assert mx.mx_gemm_q(1, 32, 64, 64, buf, f16, buf, f16, MAT, buf, None, f16, f16, buf, check=False) == mx.MX_ERR_BAD_ARG
+
+
 def test_matrix_gemm_identity_and_determinism():
     rng = np.random.default_rng(500)
     block, K, M = 32, 256, 40
