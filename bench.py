@@ -217,28 +217,29 @@ def main():
             "us": round(ms * 1e3, 2), "bytes": int(cbytes)}
         del m8s, calls
         # the whole emulated linear layer (product + MXInt bias + output quantizer) in one kernel, against the
-        # same three steps one after the other; block 16 (the paper's block length), 8-bit in and out, 4-bit weights
-        c = work[0]["case"]
-        fa16, fb16, fo16, fbias16 = mx.fmt(16, 8), mx.fmt(16, 4), mx.fmt(16, 8), mx.fmt(16, 4)
-        x16 = work[0]["xs"][0]
-        w16 = torch.randn((c.N, c.K), dtype=torch.float32, device=dev) * 0.02
-        A16 = mx.quantize_pack(x16, fa16, L)
-        B16 = mx.quantize_pack(w16, fb16, L)
-        bm16, be16 = mx.quantize(torch.randn((1, c.N), dtype=torch.float32, device=dev), fbias16)
-        o16 = torch.empty(mx.mx_packed_bytes(1, c.M, c.N, fo16, L), dtype=torch.uint8, device=dev)
-        y16 = torch.empty((c.M, c.N), dtype=torch.float32, device=dev)
+        # product followed by a separate quantize+pack of its fp32 result; 8-bit activations in and out, 4-bit
+        # weights and bias: the three prefill linears (block 32) and the first one at block 16
         if args.layout == "matrix":
-            fused = mx.bound("mx_gemm_q", 1, c.M, c.N, c.K, A16, fa16, B16, fb16, L, bm16, be16, fbias16, fo16, o16)
-            plain = mx.bound("mx_gemm", 1, c.M, c.N, c.K, A16, fa16, B16, fb16, L, y16, c.N, 0)
-            requant = mx.bound("mx_quantize_pack", y16, 1, c.M, c.N, c.N, 0, fo16, L, o16)
-            ops16 = 2.0 * c.M * c.N * c.K
-            ms_f = time_launches(lambda i: fused(), 20)
-            ms_p = time_launches(lambda i: plain(), 20)
-            ms_pq = time_launches(lambda i: (plain(), requant()), 20)
-            kernels["gemm_q_%dx%dx%d_b16_fused" % (c.M, c.N, c.K)] = {"us": round(ms_f * 1e3, 2), "TOPS": round(ops16 / ms_f / 1e9, 1)}
-            kernels["gemm_%dx%dx%d_b16" % (c.M, c.N, c.K)] = {"us": round(ms_p * 1e3, 2), "TOPS": round(ops16 / ms_p / 1e9, 1)}
-            kernels["gemm_then_quantize_pack_%dx%dx%d_b16" % (c.M, c.N, c.K)] = {"us": round(ms_pq * 1e3, 2), "TOPS": round(ops16 / ms_pq / 1e9, 1)}
-        del A16, B16, o16, y16, w16
+            for w, blk in [(work[0], 32), (work[1], 32), (work[2], 32), (work[0], 16)]:
+                c = w["case"]
+                fa_, fb_, fo_, fbias_ = mx.fmt(blk, 8), mx.fmt(blk, 4), mx.fmt(blk, 8), mx.fmt(blk, 4)
+                if blk == 32:
+                    A_, B_ = w["A"], w["B"]
+                else:
+                    A_ = mx.quantize_pack(w["xs"][0], fa_, L)
+                    B_ = mx.quantize_pack(torch.randn((c.N, c.K), dtype=torch.float32, device=dev) * 0.02, fb_, L)
+                bm_, be_ = mx.quantize(torch.randn((1, c.N), dtype=torch.float32, device=dev), fbias_)
+                o_ = torch.empty(mx.mx_packed_bytes(1, c.M, c.N, fo_, L), dtype=torch.uint8, device=dev)
+                y_ = w["Y"][0]
+                fused = mx.bound("mx_gemm_q", 1, c.M, c.N, c.K, A_, fa_, B_, fb_, L, bm_, be_, fbias_, fo_, o_)
+                plain = mx.bound("mx_gemm", 1, c.M, c.N, c.K, A_, fa_, B_, fb_, L, y_, c.N, 0)
+                requant = mx.bound("mx_quantize_pack", y_, 1, c.M, c.N, c.N, 0, fo_, L, o_)
+                ms_f = time_launches(lambda i: fused(), 20)
+                ms_pq = time_launches(lambda i: (plain(), requant()), 20)
+                kernels["linear_q_%dx%dx%d_b%d" % (c.M, c.N, c.K, blk)] = {
+                    "fused_us": round(ms_f * 1e3, 2), "fused_TOPS": round(w["ops"] / ms_f / 1e9, 1),
+                    "gemm_then_quantize_pack_us": round(ms_pq * 1e3, 2)}
+                del o_
         # decode linear, LLaMA-13B shapes: 0.5625*N*K + 4*M*K + 4*M*N bytes per call
         for M in (1, 4, 8):
             for dc in inputs.llama13b_decode(M):

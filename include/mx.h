@@ -199,8 +199,9 @@ MX_API mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const v
  * bias_mant / bias_exps: canonical form of one row of N elements in format fbias (block_rows 1, same
  * block as fo), shared by the batch; both null for no bias.  The fp32 sum is rounded once more by the
  * addition; the quantizer arithmetic is that of mx_quantize.  out_packed: mx_packed_bytes(batch, M, N,
- * fo, layout) bytes, 256-byte aligned.  MX_ERR_UNSUPPORTED unless layout is MX_LAYOUT_MATRIX and the
- * blocks of fa, fb and fo are 16 (the bfloat16 form); M must be a multiple of fo.block_rows.
+ * fo, layout) bytes, 256-byte aligned.  Built for MX_LAYOUT_MATRIX with inputs and output in the same
+ * form of it: blocks of 16 on both sides, or blocks of 32/64 on both sides with a right operand of at
+ * most 4 stored bits; anything else is MX_ERR_UNSUPPORTED.  M must be a multiple of fo.block_rows.
  */
 MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed, mx_format fa,
                     const void* B_packed, mx_format fb, int32_t layout, const uint8_t* bias_mant,

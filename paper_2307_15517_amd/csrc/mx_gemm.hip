@@ -10,6 +10,9 @@ mx_status gemm_bf16(int64_t batch, int64_t M, int64_t N, int64_t K, const void* 
 mx_status gemm_bf16_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
                       const uint8_t* bias_mant, const uint8_t* bias_exps, mx_format fbias, mx_format fo, void* out,
                       hipStream_t st);
+mx_status gemm_scaled_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, mx_format fa,
+                        const void* B, mx_format fb, const uint8_t* bias_mant, const uint8_t* bias_exps,
+                        mx_format fbias, mx_format fo, void* out, hipStream_t st);
 }  // namespace mx
 
 namespace mx {
@@ -78,13 +81,17 @@ extern "C" mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, c
     if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
     if (batch < 0 || M < 0 || N < 0 || K < 0 || K % fa.block != 0 || N % fo.block != 0 || M % fo.block_rows != 0)
         return MX_ERR_BAD_ARG;
-    // built for the block-16 form of the matrix layout on both sides
-    if (layout != MX_LAYOUT_MATRIX || fa.block != 16 || fo.block != 16) return MX_ERR_UNSUPPORTED;
+    // built for the matrix layout, inputs and output in the same form of it (blocks of 16, or of 32/64)
+    if (layout != MX_LAYOUT_MATRIX || !matrix_format_ok(fa) || !matrix_format_ok(fo)) return MX_ERR_UNSUPPORTED;
+    if ((fa.block == 16) != (fo.block == 16)) return MX_ERR_UNSUPPORTED;
     if (batch == 0 || M == 0 || N == 0) return MX_OK;
     if (!out_packed || ((uintptr_t)out_packed & 255)) return MX_ERR_BAD_ARG;
     if (K > 0 && (!A_packed || !B_packed)) return MX_ERR_BAD_ARG;
     if (((uintptr_t)A_packed & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
     if (batch > 65535) return MX_ERR_UNSUPPORTED;
-    return gemm_bf16_q(batch, M, N, K, A_packed, B_packed, bias_mant, bias_exps, fbias, fo, out_packed,
-                       (hipStream_t)stream);
+    if (fa.block == 16)
+        return gemm_bf16_q(batch, M, N, K, A_packed, B_packed, bias_mant, bias_exps, fbias, fo, out_packed,
+                           (hipStream_t)stream);
+    return gemm_scaled_q(batch, M, N, K, A_packed, fa, B_packed, fb, bias_mant, bias_exps, fbias, fo, out_packed,
+                         (hipStream_t)stream);
 }

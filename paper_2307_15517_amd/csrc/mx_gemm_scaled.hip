@@ -22,6 +22,7 @@ namespace mx {
 namespace {
 
 typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v6i __attribute__((ext_vector_type(6)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct ScaledArgs {
@@ -37,6 +38,13 @@ struct ScaledArgs {
     int64_t ldy, batch_stride_y;
     int32_t eadj;
     int32_t tiles_m, tiles_n;      // workgroup tiles along M and N
+    // quantized output (mx_gemm_q): the result leaves as a packed operand [M x N] of this layout, blocks along N
+    uint8_t* out;
+    MatGeom go;
+    const uint8_t* bias_mant;      // canonical MXInt bias [N] (one row), or null
+    const uint8_t* bias_exps;
+    int32_t wbias, bias_b, blk_bias;   // stored width, exponent bias and block size of the bias format
+    int32_t wo, bias_o, emax_o, rnd_o, brows_o, blk_o;   // output format
 };
 
 // `bytes` (16 or 4) per lane from global memory straight into LDS: lane L's bytes land at
@@ -74,7 +82,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // S: LDS stages.  The stage of step ks is free once its fragments are in registers, i.e. from
 // the barrier of step ks on, so the copy of step ks+S is issued during step ks.
 // OCC: workgroups the register and LDS budget must leave room for on one compute unit.
-template <int PA, int PB, int TM, int TN, int S, int OCC>
+// QO: 0 = fp32 result; 1 / 2 = add the bias and quantize the tile to an output format of one / two
+// mantissa pieces (Section 3.2 of the paper: the emulated operator quantizes its result; Fig. 2b: the
+// linear layer's bias is MXInt too), writing the packed operand the next product reads.
+template <int PA, int PB, int TM, int TN, int S, int OCC, int QO>
 __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     constexpr int kStages = S;
     constexpr int UA = (PA == 2) ? 2 * TM : TM;        // units of the A tile per K step
@@ -286,8 +297,120 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     wait_vmcnt<0>();                                      // the clamped tail copies must not outlive the LDS
 
     const int64_t rtA0 = (bm * 2 + wm) * RA, rtB0 = (bn * 2 + wn) * RB;
-    float* Y = g.Y + bz * g.batch_stride_y;
     const int i = lane & 31, h = lane >> 5;
+    if constexpr (QO != 0) {
+        // One row tile of the wave at a time: results -> the wave's LDS tile, row-major; then lane 32*h' + i'
+        // holds the 32 consecutive elements of row i' that a fragment of the next product's left operand
+        // gives it, and runs the quantizer of mx_quantize_pack on them.
+        static_assert(RB % 2 == 0, "a wave covers whole K steps of the output");
+        constexpr int PITCH = 32 * RB + 4;               // floats; the skew spreads the rows over the banks
+        // LDS: four tiles of 32 x PITCH floats, then the bias of the 64*TN columns (the launch sizes the
+        // allocation for whichever is larger, this or the stages)
+        __syncthreads();                                 // every wave is done reading the stages
+        float* tile = reinterpret_cast<float*>(smem) + wave * (32 * PITCH);
+        float* bias_lds = reinterpret_cast<float*>(smem) + 4 * 32 * PITCH;
+        if (g.bias_mant != nullptr) {                    // the bias of the workgroup's columns, decoded once
+            for (int c = threadIdx.x; c < 64 * TN; c += 256) {
+                const int64_t n = bn * (64 * TN) + c;
+                float bv = 0.f;
+                if (n < g.N) {
+                    const int64_t bit = n * g.wbias;
+                    const int sh = (int)(bit & 7);
+                    uint32_t code = g.bias_mant[bit >> 3];
+                    if (sh + g.wbias > 8) code |= (uint32_t)g.bias_mant[(bit >> 3) + 1] << 8;
+                    const int q = ((int)((code >> sh) << (32 - g.wbias))) >> (32 - g.wbias);
+                    bv = __builtin_ldexpf((float)q, (int)g.bias_exps[n / g.blk_bias] - g.bias_b - (g.wbias - 2));
+                }
+                bias_lds[c] = bv;
+            }
+            __syncthreads();
+        }
+        uint8_t* obase = g.out + bz * g.go.matrix;
+        const float qmax = (float)((1 << (g.wo - 1)) - 1);
+#pragma unroll
+        for (int ta = 0; ta < RA; ++ta) {
+#pragma unroll
+            for (int tb = 0; tb < RB; ++tb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    tile[(8 * (r >> 2) + 4 * h + (r & 3)) * PITCH + tb * 32 + i] = __builtin_ldexpf(acc[ta][tb][r], g.eadj);
+            __builtin_amdgcn_wave_barrier();
+            const int64_t rt = rtA0 + ta, row = rt * 32 + i;
+#pragma unroll
+            for (int ksl = 0; ksl < RB / 2; ++ksl) {
+                const int64_t ks = rtB0 / 2 + ksl;        // K step of the output operand
+                const int64_t col0 = ks * 64 + h * 32;
+                const bool inside = row < g.M && col0 < g.N;
+                float v[32];
+#pragma unroll
+                for (int q4 = 0; q4 < 8; ++q4) {
+                    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (inside) {
+                        t = *reinterpret_cast<const float4*>(tile + i * PITCH + ksl * 64 + h * 32 + 4 * q4);
+                        if (g.bias_mant != nullptr) {
+                            const float4 b = *reinterpret_cast<const float4*>(bias_lds + wn * (32 * RB) + ksl * 64 + h * 32 + 4 * q4);
+                            t.x += b.x; t.y += b.y; t.z += b.z; t.w += b.w;
+                        }
+                    }
+                    v[4 * q4] = t.x; v[4 * q4 + 1] = t.y; v[4 * q4 + 2] = t.z; v[4 * q4 + 3] = t.w;
+                }
+                uint32_t am = 0;
+#pragma unroll
+                for (int e = 0; e < 32; ++e) {
+                    const uint32_t ab = __float_as_uint(v[e]) & 0x7fffffffu;
+                    am = ab > am ? ab : am;
+                }
+                if (g.blk_o == 64) {                      // the two halves of a lane pair form one block
+                    const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
+                    am = o > am ? o : am;
+                }
+                if (g.brows_o == 2) {                     // two-row blocks: the neighbouring lane holds the other row
+                    const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);
+                    am = o > am ? o : am;
+                }
+                const int ef = (int)(am >> 23);
+                int E = ef == 0 ? -127 : ef - 127;
+                E = E < -g.bias_o ? -g.bias_o : E;
+                E = E > g.emax_o ? g.emax_o : E;
+                const int shift = (g.wo - 2) - E;
+                v16f lo0, lo1, hi0, hi1;
+#pragma unroll
+                for (int e = 0; e < 32; ++e) {
+                    const float sc = __builtin_ldexpf(v[e], shift);
+                    float r = g.rnd_o == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
+                    r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+                    float hi = 0.f, lo = r;
+                    if (QO == 2) {
+                        hi = __builtin_floorf(r * 0.0625f + 0.5f);      // h = floor((q + 8) / 16)
+                        lo = r - 16.f * hi;
+                    }
+                    lo += 0.0f;                                          // -0.0 -> +0.0
+                    if (e & 1) { lo1[e >> 1] = lo; hi1[e >> 1] = hi; }
+                    else       { lo0[e >> 1] = lo; hi0[e >> 1] = hi; }
+                }
+                if (rt < g.go.row_tiles && ks < g.go.ksteps) {
+                    const v6i fl = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(lo0, lo1, 2.0f);   // codes of piece / 2
+                    uint8_t* unit = obase + mat_unit(g.go, QO == 2 ? rt : rt >> 1, ks);
+                    const int lslot = QO == 2 ? 1 : (int)(rt & 1);
+                    *reinterpret_cast<uint4*>(unit + frag_lo(lslot, lane)) =
+                        make_uint4((uint32_t)fl[0], (uint32_t)fl[1], (uint32_t)fl[2], (uint32_t)fl[3]);
+                    *reinterpret_cast<uint2*>(unit + frag_hi(lslot, lane)) = make_uint2((uint32_t)fl[4], (uint32_t)fl[5]);
+                    if (QO == 2) {
+                        const v6i fh = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(hi0, hi1, 2.0f);
+                        *reinterpret_cast<uint4*>(unit + frag_lo(0, lane)) =
+                            make_uint4((uint32_t)fh[0], (uint32_t)fh[1], (uint32_t)fh[2], (uint32_t)fh[3]);
+                        *reinterpret_cast<uint2*>(unit + frag_hi(0, lane)) = make_uint2((uint32_t)fh[4], (uint32_t)fh[5]);
+                    }
+                    // the lane's scale byte of this K step (bytes of one dword come from different waves)
+                    obase[g.go.frag_bytes + ((rt * (g.go.ksteps / 4) + (ks >> 2)) * 64 + lane) * 4 + (ks & 3)] =
+                        inside ? (uint8_t)(E + 127) : (uint8_t)0;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+    float* Y = g.Y + bz * g.batch_stride_y;
 #pragma unroll
     for (int ta = 0; ta < RA; ++ta) {
 #pragma unroll
@@ -302,12 +425,14 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     }
 }
 
-template <int PA, int PB, int TM, int TN, int S, int OCC>
+template <int PA, int PB, int TM, int TN, int S, int OCC, int QO = 0>
 mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
     constexpr int UA = (PA == 2) ? 2 * TM : TM, UB = (PB == 2) ? 2 * TN : TN;
-    constexpr int smem = S * (UA + UB) * kUnitBytes + 2 * (2 * TM + 2 * TN) * 256;
+    constexpr int pipe = S * (UA + UB) * kUnitBytes + 2 * (2 * TM + 2 * TN) * 256;
+    constexpr int turn = QO == 0 ? 0 : 4 * 32 * (32 * TN + 4) * 4 + 64 * TN * 4;     // quantized ending
+    constexpr int smem = pipe > turn ? pipe : turn;
     static_assert(smem * OCC <= 160 * 1024, "LDS budget of one compute unit");
-    auto kern = gemm_scaled_kernel<PA, PB, TM, TN, S, OCC>;
+    auto kern = gemm_scaled_kernel<PA, PB, TM, TN, S, OCC, QO>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
@@ -329,13 +454,14 @@ mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
 // the stages are small enough, two workgroups share a compute unit (three stages each), so that
 // one workgroup's barrier and copy waits hide under the other's MFMAs; otherwise one workgroup
 // per compute unit runs with four stages.
-template <int PA, int PB>
+template <int PA, int PB, int QO = 0>
 mx_status pick_tile(ScaledArgs& g, int64_t batch, hipStream_t st) {
     const int64_t tiles = ceil_div(g.M, 128) * ceil_div(g.N, 256) * batch;
     if constexpr (PB == 1) {
-        if (tiles >= 2 * 256) return launch_scaled<PA, PB, 2, 4, 3, 2>(g, batch, st);
-        return launch_scaled<PA, PB, 2, 4, 4, 1>(g, batch, st);
+        if (tiles >= 2 * 256) return launch_scaled<PA, PB, 2, 4, 3, 2, QO>(g, batch, st);
+        return launch_scaled<PA, PB, 2, 4, 4, 1, QO>(g, batch, st);
     } else {
+        static_assert(QO == 0, "the quantized ending is built for one-piece right operands");
         return launch_scaled<PA, PB, 2, 4, 3, 1>(g, batch, st);
     }
 }
@@ -354,10 +480,36 @@ mx_status gemm_scaled(int64_t batch, int64_t M, int64_t N, int64_t K, const void
     // pieces are stored halved (2 bits in all), mantissa units are 2^-(w-2) each
     g.eadj = 2 - (fa.mant_bits - 2) - (fb.mant_bits - 2);
     g.tiles_m = g.tiles_n = 0;
+    g.out = nullptr; g.bias_mant = g.bias_exps = nullptr;
     if (ga.pieces == 2 && gb.pieces == 1) return pick_tile<2, 1>(g, batch, st);
     if (ga.pieces == 1 && gb.pieces == 1) return pick_tile<1, 1>(g, batch, st);
     if (ga.pieces == 2 && gb.pieces == 2) return pick_tile<2, 2>(g, batch, st);
     return pick_tile<1, 2>(g, batch, st);
+}
+
+// The same product with the bias added and the result quantized to `fo` (block 32 or 64, blocks along
+// N), written as the packed operand [M x N] of this layout.  Right operands of up to 4 stored bits.
+mx_status gemm_scaled_q(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, mx_format fa,
+                        const void* B, mx_format fb, const uint8_t* bias_mant, const uint8_t* bias_exps,
+                        mx_format fbias, mx_format fo, void* out, hipStream_t st) {
+    const MatGeom ga = mat_geom(M, K, fa.mant_bits), gb = mat_geom(N, K, fb.mant_bits);
+    if (gb.pieces != 1) return MX_ERR_UNSUPPORTED;
+    ScaledArgs g;
+    g.A = (const uint8_t*)A; g.B = (const uint8_t*)B; g.Y = nullptr; g.M = M; g.N = N;
+    g.unitsA = ga.units; g.unitsB = gb.units; g.tilesA = ga.row_tiles; g.tilesB = gb.row_tiles;
+    g.ksteps = ga.ksteps; g.fragA = ga.frag_bytes; g.fragB = gb.frag_bytes;
+    g.matrixA = ga.matrix; g.matrixB = gb.matrix; g.ldy = 0; g.batch_stride_y = 0;
+    g.eadj = 2 - (fa.mant_bits - 2) - (fb.mant_bits - 2);
+    g.tiles_m = g.tiles_n = 0;
+    g.out = (uint8_t*)out; g.go = mat_geom(M, N, fo.mant_bits);
+    g.bias_mant = bias_mant; g.bias_exps = bias_exps;
+    g.wbias = fbias.mant_bits; g.bias_b = (1 << (fbias.exp_bits - 1)) - 1; g.blk_bias = fbias.block;
+    g.wo = fo.mant_bits; g.bias_o = (1 << (fo.exp_bits - 1)) - 1;
+    g.emax_o = ((1 << fo.exp_bits) - 1) - g.bias_o;
+    g.rnd_o = fo.rounding; g.brows_o = fo.block_rows; g.blk_o = fo.block;
+    const int po = mat_pieces(fo.mant_bits);
+    if (ga.pieces == 2) return po == 2 ? pick_tile<2, 1, 2>(g, batch, st) : pick_tile<2, 1, 1>(g, batch, st);
+    return po == 2 ? pick_tile<1, 1, 2>(g, batch, st) : pick_tile<1, 1, 1>(g, batch, st);
 }
 
 }  // namespace mx

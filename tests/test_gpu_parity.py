@@ -793,13 +793,15 @@ def check_quantized_output(q_g, e_g, q_o, e_o, y, mag, block, w, block_rows):
     return float(same)
 
 
-@pytest.mark.parametrize("block_rows,wo", [(1, 8), (1, 4), (2, 8), (2, 5)])
-def test_gemm_q_bias_and_output_quantizer(block_rows, wo):
+@pytest.mark.parametrize("block,block_rows,wx,wo", [(16, 1, 8, 8), (16, 1, 8, 4), (16, 2, 8, 8), (16, 2, 8, 5),
+                                                    (32, 1, 8, 8), (32, 1, 8, 4), (32, 2, 4, 6), (64, 1, 8, 8),
+                                                    (64, 2, 3, 3)])
+def test_gemm_q_bias_and_output_quantizer(block, block_rows, wx, wo):
     """mx_gemm_q: product + MXInt bias + output quantizer in one kernel, against the oracle's emulated
     linear layer, and bit for bit against mx_gemm, the fp32 bias add and mx_quantize_pack run one by one."""
-    rng = np.random.default_rng(40 + wo + block_rows)
-    block, wx, ww, wbias = 16, 8, 4, 4
-    for M, K, N in [(128, 768, 3072), (70, 7 * 16, 16 * 11)]:
+    rng = np.random.default_rng(40 + wo + block_rows + block)
+    ww, wbias = 4, 4
+    for M, K, N in [(128, 768, 3072), (70, 7 * 64, 64 * 11), (300, 5 * 64, 64 * 9)]:
         x = rng.standard_normal((M, K)).astype(np.float32)
         wt = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
         bias = (rng.standard_normal(N) * 0.1).astype(np.float32)
@@ -833,7 +835,8 @@ def test_gemm_q_bias_and_output_quantizer(block_rows, wo):
             q_g, e_g, q_o, e_o, y_ref, mag, block, wo, block_rows))
     f16, f32_ = mx.fmt(16, 8), mx.fmt(32, 8)
     buf = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
-    assert mx.mx_gemm_q(1, 32, 64, 64, buf, f32_, buf, f32_, MAT, None, None, f32_, f32_, buf, check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_gemm_q(1, 32, 64, 64, buf, f32_, buf, f32_, MAT, None, None, f32_, f32_, buf, check=False) == mx.MX_ERR_UNSUPPORTED   # 8-bit right operand
+    assert mx.mx_gemm_q(1, 32, 64, 64, buf, f16, buf, f16, MAT, None, None, f16, f32_, buf, check=False) == mx.MX_ERR_UNSUPPORTED    # forms differ
     assert mx.mx_gemm_q(1, 32, 64, 64, buf, f16, buf, f16, mx.MX_LAYOUT_FRAGMENT, None, None, f16, f16, buf, check=False) == mx.MX_ERR_UNSUPPORTED
     assert mx.mx_gemm_q(1, 32, 72, 64, buf, f16, buf, f16, MAT, None, None, f16, f16, buf, check=False) == mx.MX_ERR_BAD_ARG
     assert mx.mx_gemm_q(1, 32, 64, 64, buf, f16, buf, f16, MAT, buf, None, f16, f16, buf, check=False) == mx.MX_ERR_BAD_ARG
