@@ -61,7 +61,8 @@ typedef struct {
                           With 2, rows must be even and the canonical exponent array is
                           [rows/2][cols/block]; the packed layouts repeat the byte for both rows, so
                           mx_gemm does not care.  Not supported (MX_ERR_UNSUPPORTED): mx_quantize along
-                          axis 0, mx_cast, and the activation format of mx_linear. */
+                          axis 0, mx_cast unless cols is a multiple of 32, and the activation format of
+                          mx_linear. */
 } mx_format;
 
 enum { MX_RNE = 0,  /* round to nearest, ties to the even mantissa */
@@ -143,7 +144,8 @@ MX_API mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t
  * re-derived from the largest mantissa (a block that is not normalised gains mantissa bits), the
  * mantissas are shifted left (exact) or right with fd.rounding and saturate at +-qmax of fd; the
  * exponent is clamped to fd.exp_bits.  mant and mant_out 4-byte aligned, dense, distinct buffers
- * (MX_ERR_BAD_ARG for in-place use or fs.block != fd.block); fs.rounding is ignored.
+ * (MX_ERR_BAD_ARG for in-place use, fs.block != fd.block or fs.block_rows != fd.block_rows);
+ * fs.rounding is ignored.
  */
 MX_API mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
                   mx_format fs, mx_format fd, uint8_t* mant_out, uint8_t* exps_out, void* stream);

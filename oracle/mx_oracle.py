@@ -139,13 +139,20 @@ def dequantize(q: np.ndarray, exps: np.ndarray, block: int, w: int, e: int = 8) 
 
 
 def cast(q: np.ndarray, exps: np.ndarray, block: int, ws: int, wd: int, es: int = 8, ed: int = 8,
-         rounding: int = RNE) -> Tuple[np.ndarray, np.ndarray]:
+         rounding: int = RNE, block_rows: int = 1) -> Tuple[np.ndarray, np.ndarray]:
     """MXInt (block, es, ws) -> MXInt (block, ed, wd) in integer arithmetic: mantissa extension or
     rounding shift plus exponent renormalisation (Section 4, mixed-precision paragraph).
-    q int8 [rows, cols], exps uint8 [rows, cols/block]; returns the same shapes."""
+    q int8 [rows, cols], exps uint8 [rows/block_rows, cols/block]; returns the same shapes.
+    Two-dimensional blocks are regrouped into runs, as in quantize."""
     q = np.ascontiguousarray(q, dtype=np.int8)
     exps = np.ascontiguousarray(exps, dtype=np.uint8)
     rows, cols = q.shape
+    if block_rows != 1:
+        R, nb = block_rows, cols // block
+        assert rows % R == 0 and exps.shape == (rows // R, nb)
+        qr = np.ascontiguousarray(q.reshape(rows // R, R, nb, block).transpose(0, 2, 1, 3)).reshape(rows // R, nb * R * block)
+        q2, e2 = cast(qr, exps, R * block, ws, wd, es, ed, rounding)
+        return np.ascontiguousarray(q2.reshape(rows // R, nb, R, block).transpose(0, 2, 1, 3)).reshape(rows, cols), e2
     assert exps.shape == (rows, cols // block)
     q2 = np.empty((rows, cols), np.int8)
     e2 = np.empty((rows, cols // block), np.uint8)

@@ -24,6 +24,7 @@ struct CastArgs {
     int64_t elems;             // batch * rows * cols
     int32_t bias_s, bias_d, emin_d, emax_d;
     int32_t vec;               // both mantissa arrays are 16-byte aligned
+    int64_t runs_per_row;      // two-row blocks: cols / 32
 };
 
 template <int WS, int WD, int B, int RND>
@@ -125,8 +126,105 @@ __global__ __launch_bounds__(256) void cast_kernel(CastArgs a) {
     }
 }
 
+// Two-row blocks (block shape (B, 2)): one thread converts the same 32 columns of rows 2p and 2p+1, which
+// share their exponents; the block maximum runs over both rows.  cols is a multiple of 32 here, so every
+// run is whole and dword-aligned.
+template <int WS, int WD, int B, int RND>
+__global__ __launch_bounds__(256) void cast_rows2_kernel(CastArgs a) {
+    constexpr int NB = B >= 32 ? 1 : 32 / B;
+    constexpr int BE = B >= 32 ? 32 : B;
+    constexpr int qmax = (1 << (WD - 1)) - 1;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t pairs = a.elems / (64 * a.runs_per_row);
+    const bool live = t < pairs * a.runs_per_row;
+    const int64_t pr = live ? t / a.runs_per_row : 0, rr = live ? t - pr * a.runs_per_row : 0;
+    int q[2][32];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        uint32_t in[WS + 1];
+#pragma unroll
+        for (int d = 0; d <= WS; ++d) in[d] = 0;
+        if (live) {
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(a.mant + ((2 * pr + r) * a.runs_per_row + rr) * (4 * WS));
+#pragma unroll
+            for (int d = 0; d < WS; ++d) in[d] = src[d];
+        }
+#pragma unroll
+        for (int i = 0; i < 32; ++i) q[r][i] = stream_get<WS>(in, i * WS);
+    }
+    uint32_t out[2][WD];
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int d = 0; d < WD; ++d) out[r][d] = 0;
+    const int64_t blk0 = (pr * a.runs_per_row + rr) * 32 / B;        // exponent index: [pair][block]
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        int mx = 0;
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int i = 0; i < BE; ++i) {
+                const int v = q[r][j * BE + i];
+                const int m = v < 0 ? -v : v;
+                mx = m > mx ? m : mx;
+            }
+        if (B == 64) {
+            const int o = __builtin_amdgcn_update_dpp(0, mx, 0xB1, 0xF, 0xF, true);
+            mx = o > mx ? o : mx;
+        }
+        int ebyte = 0;
+        if (live && mx != 0) {
+            const int E = (int)a.exps[blk0 + j] - a.bias_s;
+            int E2 = E - (WS - 2) + (31 - __builtin_clz((unsigned)mx));
+            E2 = E2 < a.emin_d ? a.emin_d : E2;
+            E2 = E2 > a.emax_d ? a.emax_d : E2;
+            int sh = (E - (WS - 2)) - (E2 - (WD - 2));
+            ebyte = E2 + a.bias_d;
+            sh = sh > 16 ? 16 : (sh < -16 ? -16 : sh);
+#pragma unroll
+            for (int r = 0; r < 2; ++r)
+#pragma unroll
+                for (int i = 0; i < BE; ++i) {
+                    const int v = q[r][j * BE + i];
+                    int res;
+                    if (sh >= 0) {
+                        res = v << sh;
+                    } else {
+                        const int k = -sh;
+                        if (RND == MX_RNE) res = (v + ((1 << (k - 1)) - 1) + ((v >> k) & 1)) >> k;
+                        else res = (v + ((v >> 31) & ((1 << k) - 1))) >> k;
+                    }
+                    res = res > qmax ? qmax : (res < -qmax ? -qmax : res);
+                    const int bit = (j * BE + i) * WD;
+                    const uint32_t code = (uint32_t)res & ((1u << WD) - 1u);
+                    out[r][bit >> 5] |= code << (bit & 31);
+                    if ((bit & 31) + WD > 32) out[r][(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+                }
+        }
+        if (live && (B < 64 || (rr & 1) == 0)) a.exps_out[blk0 + j] = (uint8_t)ebyte;
+    }
+    if (live) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(a.mant_out + ((2 * pr + r) * a.runs_per_row + rr) * (4 * WD));
+#pragma unroll
+            for (int d = 0; d < WD; ++d) dst[d] = out[r][d];
+        }
+    }
+}
+
 template <int WS, int WD, int B>
 mx_status launch_cast(const CastArgs& a, int rnd, hipStream_t st) {
+    if (a.runs_per_row > 0) {
+        const int64_t items = a.elems / 64;
+        if (ceil_div(items, 256) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+        dim3 grid((unsigned)ceil_div(items, 256));
+        if (rnd == MX_RNE) hipLaunchKernelGGL((cast_rows2_kernel<WS, WD, B, MX_RNE>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((cast_rows2_kernel<WS, WD, B, MX_RTZ>), grid, dim3(256), 0, st, a);
+        MX_HIP_LAUNCH_CHECK();
+        return MX_OK;
+    }
     const int64_t runs = ceil_div(a.elems, 32);
     if (ceil_div(runs, 256) > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     dim3 grid((unsigned)ceil_div(runs, 256));
@@ -170,7 +268,9 @@ extern "C" mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t b
                              mx_format fs, mx_format fd, uint8_t* mant_out, uint8_t* exps_out, void* stream) {
     if (!format_ok_quant(fs) || !format_ok_quant(fd) || fs.block != fd.block) return MX_ERR_BAD_ARG;
     if (batch < 0 || rows < 0 || cols < 0 || cols % fs.block != 0) return MX_ERR_BAD_ARG;
-    if (fs.block_rows != 1 || fd.block_rows != 1) return MX_ERR_UNSUPPORTED;
+    if (fs.block_rows != fd.block_rows) return MX_ERR_BAD_ARG;
+    if (fs.block_rows == 2 && rows % 2 != 0) return MX_ERR_BAD_ARG;
+    if (fs.block_rows == 2 && cols % 32 != 0) return MX_ERR_UNSUPPORTED;     // two-row blocks: whole 32-element runs per row
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!mant || !exps || !mant_out || !exps_out) return MX_ERR_BAD_ARG;
     if (((uintptr_t)mant & 3) || ((uintptr_t)mant_out & 3)) return MX_ERR_BAD_ARG;
@@ -179,6 +279,7 @@ extern "C" mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t b
     a.mant = mant; a.exps = exps; a.mant_out = mant_out; a.exps_out = exps_out;
     a.elems = batch * rows * cols;
     a.vec = ((((uintptr_t)mant) | ((uintptr_t)mant_out)) & 15) == 0 ? 1 : 0;
+    a.runs_per_row = fs.block_rows == 2 ? cols / 32 : 0;
     a.bias_s = (1 << (fs.exp_bits - 1)) - 1;
     a.bias_d = (1 << (fd.exp_bits - 1)) - 1;
     a.emin_d = -a.bias_d;

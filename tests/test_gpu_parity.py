@@ -238,7 +238,8 @@ def test_two_row_blocks_rejections():
     out = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
     assert mx.mx_quantize(xf, 1, 7, 64, 64, 0, 1, f2, buf, out, check=False) == mx.MX_ERR_BAD_ARG          # odd rows
     assert mx.mx_quantize(xf, 1, 32, 16, 16, 0, 0, f2, buf, out, check=False) == mx.MX_ERR_UNSUPPORTED     # along the rows
-    assert mx.mx_cast(buf, buf, 1, 8, 64, f2, mx.fmt(16, 4, block_rows=2), out, out, check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_cast(buf, buf, 1, 8, 48, f2, mx.fmt(16, 4, block_rows=2), out, out, check=False) == mx.MX_ERR_UNSUPPORTED   # cols % 32
+    assert mx.mx_cast(buf, buf, 1, 8, 64, f2, mx.fmt(16, 4), out, out, check=False) == mx.MX_ERR_BAD_ARG                     # block_rows differ
     assert mx.mx_quantize(xf, 1, 8, 64, 64, 0, 1, mx.fmt(16, 8, block_rows=3), buf, out, check=False) == mx.MX_ERR_BAD_ARG
     y = torch.zeros((2, 64), dtype=torch.float32, device=DEV)
     assert mx.mx_linear(xf, 2, 64, 64, f2, buf, buf, 64, mx.fmt(16, 4), mx.MX_LAYOUT_FRAGMENT, y, 64,
@@ -249,11 +250,11 @@ def test_two_row_blocks_rejections():
 # ----------------------------------------------------------------------------------------------
 # Width cast inside the format (bit-exact against the oracle's integer cast)
 # ----------------------------------------------------------------------------------------------
-def check_cast(q, ex, block, ws, wd, es=8, ed=8, rounding=mx.MX_RNE, batch=1):
+def check_cast(q, ex, block, ws, wd, es=8, ed=8, rounding=mx.MX_RNE, batch=1, block_rows=1):
     rows, cols = q.shape[-2], q.shape[-1]
     q2 = q.reshape(-1, cols)
-    want_q, want_e = orc.cast(q2, ex.reshape(-1, cols // block), block, ws, wd, es, ed, rounding)
-    fs, fd = mx.fmt(block, ws, es), mx.fmt(block, wd, ed, rounding)
+    want_q, want_e = orc.cast(q2, ex.reshape(-1, cols // block), block, ws, wd, es, ed, rounding, block_rows=block_rows)
+    fs, fd = mx.fmt(block, ws, es, block_rows=block_rows), mx.fmt(block, wd, ed, rounding, block_rows=block_rows)
     mant = dev(orc.pack_bits(q2, ws).reshape(-1))
     got_m, got_e = mx.cast(mant, dev(ex.reshape(-1)), batch, rows, cols, fs, fd)
     torch.cuda.synchronize()
@@ -294,6 +295,18 @@ def test_cast_exponent_widths_batch_and_workload_shape():
     m4, x4 = mx.cast(m8, x8, 1, x.shape[0], x.shape[1], f8, f4)
     torch.cuda.synchronize()
     assert np.array_equal(host(m4), orc.pack_bits(q4, 4).reshape(-1)) and np.array_equal(host(x4), e4.reshape(-1))
+
+
+@pytest.mark.parametrize("block", [8, 16, 32, 64])
+def test_cast_two_row_blocks(block):
+    rng = np.random.default_rng(960 + block)
+    for ws, wd in [(8, 4), (4, 8), (6, 3), (3, 7), (5, 5), (8, 8), (2, 2)]:
+        rows, cols = 2 * 19, (6 * 64 if block == 64 else 5 * 64 + 32)
+        q = rng.integers(-(2 ** (ws - 1)), 2 ** (ws - 1), size=(2, rows, cols)).astype(np.int8)
+        q[:, ::4] //= 8
+        q[:, 6:8] = 0
+        ex = rng.integers(0, 256, size=(2, rows // 2, cols // block)).astype(np.uint8)
+        check_cast(q, ex, block, ws, wd, rounding=mx.MX_RTZ if ws == 6 else mx.MX_RNE, batch=2, block_rows=2)
 
 
 def test_cast_rejects_bad_arguments():

@@ -518,3 +518,17 @@ def test_linear_q_hand_worked_and_composition():
         assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
         q2, e2 = orc.quantize(y.astype(np.float32), 16, 6, block_rows=br)
         assert np.array_equal(qo, q2) and np.array_equal(eo, e2)
+
+
+def test_cast_two_row_blocks_equals_quantizing_the_exact_values():
+    rng = np.random.default_rng(2024)
+    block, R = 16, 2
+    for ws, wd in [(8, 4), (4, 8), (6, 3), (5, 5)]:
+        q = rng.integers(-(2 ** (ws - 1)), 2 ** (ws - 1), size=(12, 4 * block)).astype(np.int8)
+        q[::4] //= 4
+        ex = rng.integers(40, 200, size=(6, 4)).astype(np.uint8)
+        x = orc.dequantize(q, orc.row_exps(ex, R), block, ws).astype(np.float32)
+        for rounding in (orc.RNE, orc.RTZ):
+            want_q, want_e = orc.quantize(x, block, wd, 8, rounding, block_rows=R)
+            got_q, got_e = orc.cast(q, ex, block, ws, wd, 8, 8, rounding, block_rows=R)
+            assert np.array_equal(got_q, want_q) and np.array_equal(got_e, want_e)
