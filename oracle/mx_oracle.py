@@ -232,3 +232,37 @@ def linear_q(x: np.ndarray, wt: np.ndarray, bias: Optional[np.ndarray], block: i
         mag = mag + np.abs(bv)
     qo, eo = quantize(y.astype(np.float32), block, wo, e, rounding, block_rows=block_rows)
     return qo, eo, y, mag
+
+
+def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, wk: int, wp: int, wv: int,
+              scale: float, e: int = 8, rounding: int = RNE, rows: Optional[Tuple[int, int]] = None):
+    """One head of attention with every matrix product taken in MXInt (Fig. 1: the two products of the
+    attention layer have both operands quantized; Section 3.2: an emulated operator quantizes its inputs
+    and computes on the quantized values; softmax itself stays in floating point).
+
+    Q [Sq,D], K [Sk,D], V [Sk,D] float32.  Steps, in the order of the definition:
+      1. Q and K are quantized in blocks along D;  S = MXInt product Q K^T                       [Sq,Sk]
+      2. P = softmax(scale * S) along the keys, in float64, then held as float32 (the quantizer's input type)
+      3. P is quantized in blocks along the keys, V in blocks along the keys (down its columns)
+      4. O = MXInt product P V                                                                   [Sq,D]
+    Returns O float64 [Sq,D] and a dict with the intermediate values the tests derive tolerances from:
+    S, S_mag (sum_b |term_b| of step 1), P (float64), pq/pe and vq/ve (the quantized operands of step 4)
+    and O_mag.  rows=(begin,end) restricts the query rows that are computed (others are NaN)."""
+    Q = np.ascontiguousarray(Q, np.float32)
+    K = np.ascontiguousarray(K, np.float32)
+    V = np.ascontiguousarray(V, np.float32)
+    r0, r1 = (0, Q.shape[0]) if rows is None else rows
+    qq, qe = quantize(Q[r0:r1], block, wq, e, rounding)
+    kq, ke = quantize(K, block, wk, e, rounding)
+    S, s_mag = gemm(qq, qe, wq, kq, ke, wk, block, e, want_mag=True)
+    Z = np.float64(scale) * S
+    Z = Z - Z.max(axis=1, keepdims=True)
+    P = np.exp(Z)
+    P = P / P.sum(axis=1, keepdims=True)
+    pq, pe = quantize(P.astype(np.float32), block, wp, e, rounding)
+    vq, ve = quantize(V, block, wv, e, rounding, axis=0)          # the quantization of V^T: [D, Sk]
+    Osub, o_mag = gemm(pq, pe, wp, vq, ve, wv, block, e, want_mag=True)
+    O = np.full((Q.shape[0], V.shape[1]), np.nan, np.float64)
+    O[r0:r1] = Osub
+    return O, {"S": S, "S_mag": s_mag, "P": P, "pq": pq, "pe": pe, "vq": vq, "ve": ve, "O_mag": o_mag,
+               "rows": (r0, r1)}

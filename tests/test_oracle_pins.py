@@ -532,3 +532,95 @@ def test_cast_two_row_blocks_equals_quantizing_the_exact_values():
             want_q, want_e = orc.quantize(x, block, wd, 8, rounding, block_rows=R)
             got_q, got_e = orc.cast(q, ex, block, ws, wd, 8, 8, rounding, block_rows=R)
             assert np.array_equal(got_q, want_q) and np.array_equal(got_e, want_e)
+
+
+# ----------------------------------------------------------------------------------------------
+# Attention with both products in MXInt (Fig. 1; Section 3.2): closed forms and hand-worked rows
+# ----------------------------------------------------------------------------------------------
+def _vdeq(V, block, wv):
+    vq, ve = orc.quantize(V, block, wv, axis=0)               # quantization of V^T
+    return orc.dequantize(vq, ve, block, wv).T                # [Sk, D]
+
+
+def test_attention_uniform_scores_average_the_values():
+    """All scores equal -> every probability is 1/Sk; with Sk a power of two that is an MXInt value, so the
+    output is exactly the mean over the keys of the quantized V."""
+    rng = np.random.default_rng(5)
+    Sk, D = 32, 48
+    Q = np.zeros((5, D), np.float32)
+    K = rng.standard_normal((Sk, D)).astype(np.float32)
+    V = rng.standard_normal((Sk, D)).astype(np.float32)
+    for wp in (2, 5, 8):
+        O, info = orc.attention(Q, K, V, 16, 8, 8, wp, 6, scale=0.3)
+        assert np.all(info["P"] == 1.0 / Sk)
+        want = _vdeq(V, 16, 6).sum(axis=0) / Sk               # dyadic numbers: exact in float64
+        assert np.array_equal(O, np.broadcast_to(want, O.shape))
+
+
+def test_attention_dominant_key_selects_its_value_row():
+    """Query i matches key perm(i) by a margin of 2000: softmax is exactly one-hot in float64, the quantized
+    probability is exactly 1, and row i of the output is row perm(i) of the quantized V.  A softmax along the
+    wrong axis, a transposed operand or a swapped index would pick other rows."""
+    rng = np.random.default_rng(6)
+    n = 32
+    perm = rng.permutation(n)
+    K = np.eye(n, dtype=np.float32)
+    Q = np.zeros((n, n), np.float32)
+    Q[np.arange(n), perm] = 2000.0                            # 125 * 2^4: exact at width 8
+    V = rng.standard_normal((n, 16)).astype(np.float32)
+    O, info = orc.attention(Q, K, V, 16, 8, 8, 4, 8, scale=1.0)
+    onehot = np.zeros((n, n))
+    onehot[np.arange(n), perm] = 1.0
+    assert np.array_equal(info["P"], onehot)
+    assert np.array_equal(O, _vdeq(V, 16, 8)[perm])
+
+
+def test_attention_hand_worked_three_quarters():
+    """Scores (2, 1, -1024 x 14) with scale ln 3: probabilities (3/4, 1/4, 0, ...).
+    Width 4: E = -1, mantissas 6 and 2 (0.75 and 0.25 exactly)  -> O = 0.75 v0 + 0.25 v1.
+    Width 2: 0.75 * 2 = 1.5 rounds to 2 and is clamped to 1; 0.25 * 2 = 0.5 is a tie and goes to the even
+    mantissa 0                                                  -> O = 0.5 v0."""
+    Sk, D = 16, 16
+    K = np.zeros((Sk, D), np.float32)
+    K[:, 0] = -1024.0
+    K[0, 0], K[1, 0] = 2.0, 1.0
+    Q = np.zeros((3, D), np.float32)
+    Q[:, 0] = 1.0
+    V = np.zeros((Sk, D), np.float32)
+    V[0, :4] = [1.0, -2.0, 0.5, 4.0]
+    V[1, :4] = [3.0, 1.0, -0.5, -4.0]
+    V[2:, :] = 7.0                                            # must not leak in: its probability is 0
+    O, info = orc.attention(Q, K, V, 16, 8, 8, 4, 8, scale=math.log(3.0))
+    assert np.allclose(info["P"][:, :2], [[0.75, 0.25]] * 3, rtol=0, atol=1e-15)
+    assert info["pq"][0, :3].tolist() == [6, 2, 0] and info["pe"][0, 0] == 127 - 1
+    assert np.array_equal(O[:, :4], [[1.5, -1.25, 0.25, 2.0]] * 3)
+    assert np.all(O[:, 4:] == 0.0)
+    O2, info2 = orc.attention(Q, K, V, 16, 8, 8, 2, 8, scale=math.log(3.0))
+    assert info2["pq"][0, :3].tolist() == [1, 0, 0]
+    assert np.array_equal(O2[:, :4], [[0.5, -1.0, 0.25, 2.0]] * 3)
+
+
+def test_attention_steps_against_library_routines():
+    """Step by step against routines that are not the oracle's own: scores against the float matmul of the
+    dequantized operands, softmax against scipy's, the second product against the float matmul of the
+    dequantized probabilities and values; and the row window returns the same rows."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(7)
+    Sq, Sk, D = 24, 80, 64
+    Q = rng.standard_normal((Sq, D)).astype(np.float32)
+    K = rng.standard_normal((Sk, D)).astype(np.float32)
+    V = rng.standard_normal((Sk, D)).astype(np.float32)
+    Q[:, 3] *= 50.0
+    O, info = orc.attention(Q, K, V, 16, 7, 6, 5, 3, scale=D ** -0.5)
+    qq, qe = orc.quantize(Q, 16, 7)
+    kq, ke = orc.quantize(K, 16, 6)
+    S = orc.dequantize(qq, qe, 16, 7) @ orc.dequantize(kq, ke, 16, 6).T
+    assert np.allclose(info["S"], S, rtol=1e-12, atol=1e-12)
+    P = softmax(S * D ** -0.5, axis=1)
+    assert np.allclose(info["P"], P, rtol=1e-12, atol=1e-300)
+    assert np.allclose(info["P"].sum(axis=1), 1.0, rtol=1e-13)
+    pd = orc.dequantize(info["pq"], info["pe"], 16, 5)
+    assert np.all(np.abs(pd - P) <= 2.0 ** (np.floor(np.log2(P.reshape(Sq, -1, 16).max(axis=2))) - 3).repeat(16, axis=1))
+    assert np.allclose(O, pd @ _vdeq(V, 16, 3), rtol=1e-12, atol=1e-12)
+    O2, _ = orc.attention(Q, K, V, 16, 7, 6, 5, 3, scale=D ** -0.5, rows=(8, 16))
+    assert np.array_equal(O2[8:16], O[8:16]) and np.all(np.isnan(O2[:8])) and np.all(np.isnan(O2[16:]))
