@@ -305,6 +305,14 @@ def main():
         ms = time_launches(lambda i: mx.mx_gemm(heads, seq, dim, seq, Ap, fpp, Bv, fv, LA, Od, dim, seq * dim), 10)
         attn_entry("output_gemm", ms, Ap.numel() + Bv.numel() + 4 * n_el, 2.0 * heads * seq * seq * dim)
         del Ss, Ps, Ap
+        # the same from packed Q, K, V^T to O in one kernel (scores and probabilities stay on chip); the
+        # operation count is that of the two products of the definition
+        if LA == mx.MX_LAYOUT_MATRIX:
+            Ods = [torch.empty((heads, seq, dim), dtype=torch.float32, device=dev) for _ in range(2)]
+            ms = time_launches(lambda i: mx.mx_attention(heads, seq, seq, dim, Aq, fq, Bk, fk, Bv, fv, fpp, dim ** -0.5,
+                                                         LA, Ods[i % 2], dim, seq * dim), 10)
+            attn_entry("fused_scores_softmax_quantize_output", ms, Aq.numel() + Bk.numel() + Bv.numel() + 4 * n_el,
+                       4.0 * heads * seq * seq * dim)
 
     # ---------------------------------------------------------------- the oracle on the host cores
     cpu = None

@@ -210,6 +210,34 @@ MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const
                     const uint8_t* bias_exps, mx_format fbias, mx_format fo, void* out_packed, void* stream);
 
 /*
+ * Attention with both matrix products in MXInt (Fig. 1: the two products of the attention layer take
+ * quantized operands; Section 3.2: an emulated operator computes on quantized inputs), per batch
+ * entry (head) b, in one kernel:
+ *     S  = Q K^T                     MXInt x MXInt product as in mx_gemm                      [Sq x Sk]
+ *     P  = softmax(scale * S)        along the keys, in fp32
+ *     P^ = MXInt(P, fp)              blocks of fp.block along the keys, the arithmetic of mx_quantize
+ *     O  = P^ V                      MXInt x MXInt product as in mx_gemm                      [Sq x D]
+ * Neither S nor P goes through memory (at 32 heads x 2048 x 2048 they are 537 MB each in fp32).
+ * Q_packed: [batch][Sq x D] in format fq and K_packed: [batch][Sk x D] in fk, blocks along D.
+ * Vt_packed: [batch][D x Sk] in fv: V quantized in blocks along the keys (mx_quantize with axis 0)
+ *   and packed as a D x Sk matrix, i.e. the right operand mx_gemm would take for P V.
+ * All three come from mx_pack / mx_quantize_pack (device, 256-byte aligned, padding as written there).
+ * fp: format of P^ (fp.block == fv.block, fp.exp_bits == fv.exp_bits); P^ is never stored.
+ * O: device fp32, element (b, i, d) at O[b*o_batch_stride + i*ldo + d], ldo >= D.
+ * Sk >= 1, Sk a multiple of fp.block, D a multiple of fq.block; scale finite.
+ * Numerics: S and O accumulate in fp32 like mx_gemm.  P is computed in fp32 with the hardware's
+ * exp2/log2 and differs from the exactly rounded softmax of S by a few 1e-6 relative (plus the
+ * accumulation error of S times scale); a probability that close to a rounding tie of the quantizer,
+ * or a block maximum that close to a power of two, can take the neighbouring mantissa or exponent.
+ * Blocks of P^ whose elements are below 2^-126 count as zero.
+ * Built for MX_LAYOUT_MATRIX with blocks of 16 (block_rows 1) in all four formats and D <= 128;
+ * anything else is MX_ERR_UNSUPPORTED.
+ */
+MX_API mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t D, const void* Q_packed, mx_format fq,
+                       const void* K_packed, mx_format fk, const void* Vt_packed, mx_format fv, mx_format fp,
+                       float scale, int32_t layout, float* O, int64_t ldo, int64_t o_batch_stride, void* stream);
+
+/*
  * Linear layer on fp32 activations for decode (M <= 8): quantizes x [M x K] with fx
  * on the fly (same arithmetic as mx_quantize, axis 1), then the product above
  * against B_packed [N x K].  The result equals mx_quantize + mx_pack + mx_gemm.

@@ -22,7 +22,7 @@ MX_LAYOUT_MATRIX = 1
 
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
            "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
-           "mx_gemm_q", "mx_linear")
+           "mx_gemm_q", "mx_attention", "mx_linear")
 
 
 class mx_format(ctypes.Structure):
@@ -71,9 +71,11 @@ def load() -> ctypes.CDLL:
     lib.mx_unpack.argtypes = [vp, i64, i64, i64, mx_format, i32, vp, vp, vp]
     lib.mx_gemm.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, i64, i64, vp]
     lib.mx_gemm_q.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, vp, mx_format, mx_format, vp, vp]
+    lib.mx_attention.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, vp, mx_format, mx_format,
+                                 ctypes.c_float, i32, vp, i64, i64, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
     for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
-                 "mx_gemm_q", "mx_linear"):
+                 "mx_gemm_q", "mx_attention", "mx_linear"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -182,6 +184,15 @@ def mx_gemm_q(batch, M, N, K, A_packed, fa, B_packed, fb, layout, bias_mant, bia
                          fbias, fo, _p(out_packed), _stream(stream))
     if check:
         _raise(s, "mx_gemm_q")
+    return s
+
+
+def mx_attention(batch, Sq, Sk, D, Q_packed, fq, K_packed, fk, Vt_packed, fv, fp, scale, layout, O, ldo,
+                 o_batch_stride, stream=None, check: bool = True) -> int:
+    s = load().mx_attention(batch, Sq, Sk, D, _p(Q_packed), fq, _p(K_packed), fk, _p(Vt_packed), fv, fp,
+                            float(scale), layout, _p(O), ldo, o_batch_stride, _stream(stream))
+    if check:
+        _raise(s, "mx_attention")
     return s
 
 

@@ -868,3 +868,171 @@ def test_matrix_gemm_identity_and_determinism():
     torch.cuda.synchronize()
     assert np.array_equal(host(y)[0].astype(np.float64), orc.dequantize(qa, ea, block, 8))
     assert torch.equal(y, y2)
+
+
+# ----------------------------------------------------------------------------------------------
+# mx_attention: both products and the quantizer of the probabilities in one kernel
+# ----------------------------------------------------------------------------------------------
+def attention_bound(info, wp, wv, scale, rounding, e=8, block=16):
+    """Bound on |O_kernel - O_oracle| per element, from the oracle's intermediate values only.
+
+    The kernel's probabilities are fp32 values P(1 + d) with |d| <= eps: hardware exp2/log2 and the
+    rounding of their arguments (<= 1e-5 for arguments up to a few hundred), plus the fp32 accumulation
+    error of the scores (<= 1e-6 of sum|terms|, far inside the product tolerance) carried through exp
+    and through the normalisation.
+    A mantissa of P^ can therefore differ from the oracle's by one step where P / step is within eps of a
+    rounding boundary, and a whole block by up to two steps where its maximum is within eps of a power of
+    two.  Those deviations times |V^|, plus the product tolerance of the second product, bound the output.
+    Returns (bound [R, D], fraction of mantissas that may differ)."""
+    P = info["P"].astype(np.float32).astype(np.float64)
+    R, Sk = P.shape
+    bias = 2 ** (e - 1) - 1
+    # d P_k / P_k = dz_k - sum_j P_j dz_j with |dz| <= |scale| * 1e-6 * sum|terms| of that score
+    dz = abs(scale) * 1e-6 * info["S_mag"]
+    eps = 1e-5 + dz + (info["P"] * dz).sum(axis=1, keepdims=True)
+    E = info["pe"].astype(np.int64) - bias                                   # [R, Sk/block]
+    step = np.repeat(np.ldexp(1.0, E - (wp - 2)), block, axis=1)
+    x = P / step
+    edge = np.floor(x) + 0.5 if rounding == orc.RNE else np.round(x)        # nearest rounding boundary
+    may = (np.abs(x - edge) <= eps * np.maximum(x, 1.0)) & (x < 2 ** (wp - 1))
+    if rounding == orc.RTZ:
+        may &= x >= 0.5                                                      # nothing below zero to fall to
+    amax = P.reshape(R, -1, block).max(axis=2)
+    frac = amax / np.ldexp(1.0, E)                                           # in [1, 2) unless the exponent is clamped
+    eps_b = eps.reshape(R, -1, block).max(axis=2)
+    amb = ((np.abs(frac - 1.0) <= 2 * eps_b) | (np.abs(frac - 2.0) <= 4 * eps_b)) & (amax > 0)
+    dev_ = np.where(may, step, 0.0) + np.repeat(np.where(amb, 2.0, 0.0), block, axis=1) * step
+    vabs = np.abs(orc.dequantize(info["vq"], info["ve"], block, wv, e)).T    # [Sk, D]
+    pabs = np.abs(orc.dequantize(info["pq"], info["pe"], block, wp, e))
+    bound = TOL * info["O_mag"] + 1e-6 * (pabs @ vabs) + dev_ @ vabs + F32_TINY
+    return bound, float(may.mean() + amb.mean())
+
+
+def run_attention(Q, K, V, widths, scale, heads_checked=None, rows=None, rounding=mx.MX_RNE, e_pv=8, max_maybe=1e-2):
+    """Q [H,Sq,D], K, V [H,Sk,D] float32 numpy.  Returns the worst error as a fraction of its bound."""
+    wq, wk, wp, wv = widths
+    H, Sq, D = Q.shape
+    Sk = K.shape[1]
+    fq, fk = mx.fmt(16, wq, 8, rounding), mx.fmt(16, wk, 8, rounding)
+    fp_, fv = mx.fmt(16, wp, e_pv, rounding), mx.fmt(16, wv, e_pv, rounding)
+    A = mx.quantize_pack(dev(Q), fq, MAT)
+    B = mx.quantize_pack(dev(K), fk, MAT)
+    vm, ve = mx.quantize(dev(V), fv, axis=0)                                 # canonical form of V^T
+    Bv = mx.pack(vm, ve, H, D, Sk, fv, MAT)
+    O = torch.full((H, Sq, D + 4), 7.0, dtype=torch.float32, device=DEV)     # row pitch > D: the gap must survive
+    mx.mx_attention(H, Sq, Sk, D, A, fq, B, fk, Bv, fv, fp_, scale, MAT, O, D + 4, Sq * (D + 4))
+    torch.cuda.synchronize()
+    Oh = host(O)
+    assert np.all(Oh[:, :, D:] == 7.0)
+    worst = 0.0
+    for hd in (range(H) if heads_checked is None else heads_checked):
+        # the oracle re-quantizes V with exp_bits e_pv; Q and K keep 8 exponent bits
+        o_ref, info = orc_attention(Q[hd], K[hd], V[hd], wq, wk, wp, wv, scale, e_pv, rounding, rows)
+        r0, r1 = info["rows"]
+        bound, maybe = attention_bound(info, wp, wv, scale, rounding, e_pv)
+        assert maybe < max_maybe, "the tolerance would excuse too many mantissas (%.3g)" % maybe
+        err = np.abs(Oh[hd, r0:r1, :D].astype(np.float64) - o_ref[r0:r1])
+        ratio = err / bound
+        assert np.all(ratio <= 1.0), "head %d: worst error %.3g of its bound (widths %s)" % (hd, ratio.max(), widths)
+        # the tolerance is far below the size of the result: a wrong key order, row or scale cannot pass
+        if max_maybe <= 1e-2:
+            assert np.median(bound) < 1e-3 * np.abs(o_ref[r0:r1]).max()
+        worst = max(worst, float(ratio.max()))
+    return worst
+
+
+def orc_attention(Q, K, V, wq, wk, wp, wv, scale, e_pv, rounding, rows):
+    """orc.attention with a separate exponent width for P and V (the oracle function takes one width for
+    all four tensors; with 8 bits everywhere this is the same call)."""
+    if e_pv == 8:
+        return orc.attention(Q, K, V, 16, wq, wk, wp, wv, scale, 8, rounding, rows)
+    r0, r1 = (0, Q.shape[0]) if rows is None else rows
+    qq, qe = orc.quantize(Q[r0:r1], 16, wq, 8, rounding)
+    kq, ke = orc.quantize(K, 16, wk, 8, rounding)
+    S, s_mag = orc.gemm(qq, qe, wq, kq, ke, wk, 16, want_mag=True)
+    from scipy.special import softmax
+    P = softmax(np.float64(scale) * S, axis=1)
+    pq, pe = orc.quantize(P.astype(np.float32), 16, wp, e_pv, rounding)
+    vq, ve = orc.quantize(V, 16, wv, e_pv, rounding, axis=0)
+    Osub, o_mag = orc.gemm(pq, pe, wp, vq, ve, wv, 16, e_pv, want_mag=True)
+    O = np.full((Q.shape[0], V.shape[1]), np.nan)
+    O[r0:r1] = Osub
+    return O, {"S": S, "S_mag": s_mag, "P": P, "pq": pq, "pe": pe, "vq": vq, "ve": ve, "O_mag": o_mag, "rows": (r0, r1)}
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 5])
+def test_attention_fused_reduced_workload(seed):
+    """The attention workload at reduced size, widths drawn by seed; 300 queries (ragged last tile of 32 and
+    of the workgroup's 256) against 272 keys (a ragged tile of 32 keys)."""
+    heads, Sq, Sk, dim = 3, 300, 272, 128
+    widths = inputs.attention_widths(seed)
+    Q, _, _ = inputs.attention_qkv(seed, heads, Sq, dim)
+    _, K, V = inputs.attention_qkv(seed + 50, heads, Sk, dim)
+    say("attention widths", widths, "worst/bound", run_attention(Q, K, V, widths, dim ** -0.5))
+
+
+@pytest.mark.parametrize("Sq,Sk,dim", [(1, 16, 16), (33, 48, 32), (64, 2080, 64), (40, 96, 96), (257, 32, 48),
+                                        (96, 160, 112)])
+def test_attention_fused_shapes(Sq, Sk, dim):
+    rng = np.random.default_rng(Sq * 1000 + Sk)
+    Q = rng.standard_normal((2, Sq, dim)).astype(np.float32)
+    K = rng.standard_normal((2, Sk, dim)).astype(np.float32)
+    V = (rng.standard_normal((2, Sk, dim)) * rng.choice([0.01, 1.0, 30.0], size=(2, 1, dim))).astype(np.float32)
+    say("worst/bound", run_attention(Q, K, V, (8, 8, 6, 5), 0.7 * dim ** -0.5))
+
+
+@pytest.mark.parametrize("rounding,e_pv,wp", [(mx.MX_RTZ, 8, 5), (mx.MX_RNE, 4, 8), (mx.MX_RNE, 8, 2), (mx.MX_RTZ, 5, 3)])
+def test_attention_fused_rounding_and_exponent_width_of_p(rounding, e_pv, wp):
+    """Truncation for P and V; a narrow exponent for P and V (probabilities below 2^-bias share the lowest
+    exponent and lose their low bits); ternary probabilities."""
+    rng = np.random.default_rng(77)
+    Q = rng.standard_normal((2, 70, 64)).astype(np.float32)
+    K = rng.standard_normal((2, 144, 64)).astype(np.float32)
+    V = rng.standard_normal((2, 144, 64)).astype(np.float32)
+    say("worst/bound", run_attention(Q, K, V, (7, 7, wp, 6), 0.5, rounding=rounding, e_pv=e_pv))
+
+
+def test_attention_fused_peaked_and_flat_rows():
+    """Rows whose softmax is one-hot (a key matching the query by a wide margin), rows with all scores
+    equal, and ordinary rows, in one call: the exact cases of the oracle's pins, through the kernel.  Their
+    probabilities are powers of two, i.e. they sit exactly on the quantizer's exponent boundary, so for
+    those 32 rows the bound allows either exponent (two steps per element)."""
+    rng = np.random.default_rng(8)
+    Sq, Sk, dim = 64, 64, 64
+    K = rng.standard_normal((1, Sk, dim)).astype(np.float32)
+    Q = rng.standard_normal((1, Sq, dim)).astype(np.float32)
+    Q[0, :16] = 0.0                                      # flat rows: P = 1/64 exactly
+    Q[0, 16:32] = 40.0 * K[0, rng.permutation(Sk)[:16]]  # peaked rows
+    V = rng.standard_normal((1, Sk, dim)).astype(np.float32)
+    say("worst/bound", run_attention(Q, K, V, (8, 8, 7, 8), 1.0, max_maybe=0.6))
+
+
+def test_attention_fused_full_size_sampled_heads_and_rows():
+    """32 heads x 2048 x 2048 x 128, widths of seed 0, in the launch the benchmark times; the oracle takes two
+    heads and a window of query rows each."""
+    heads, seq, dim, seed = 32, 2048, 128, 0
+    Q, K, V = inputs.attention_qkv(seed, heads, seq, dim)
+    for hd, rows in ((0, (0, 40)), (31, (1990, 2048))):
+        w = run_attention(Q, K, V, inputs.attention_widths(seed), dim ** -0.5, heads_checked=[hd], rows=rows)
+        say("head", hd, "rows", rows, "worst/bound", w)
+
+
+def test_attention_rejections():
+    f = mx.fmt(16, 8)
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device=DEV)
+    O = torch.zeros((64, 128), dtype=torch.float32, device=DEV)
+    call = lambda Sq=64, Sk=64, D=128, fq=f, fk=f, fv=f, fp_=f, layout=MAT, scale=1.0, ldo=128: mx.mx_attention(
+        1, Sq, Sk, D, buf, fq, buf, fk, buf, fv, fp_, scale, layout, O, ldo, 64 * 128, check=False)
+    assert call() == mx.MX_OK
+    assert call(Sk=0) == mx.MX_ERR_BAD_ARG
+    assert call(Sk=40) == mx.MX_ERR_BAD_ARG                 # not whole blocks of keys
+    assert call(D=120) == mx.MX_ERR_BAD_ARG
+    assert call(ldo=64) == mx.MX_ERR_BAD_ARG
+    assert call(scale=float("nan")) == mx.MX_ERR_BAD_ARG
+    assert call(fk=mx.fmt(32, 8)) == mx.MX_ERR_BAD_ARG      # Q and K must share the block size
+    assert call(fq=mx.fmt(32, 4), fk=mx.fmt(32, 4), D=128) == mx.MX_ERR_UNSUPPORTED
+    assert call(layout=mx.MX_LAYOUT_FRAGMENT) == mx.MX_ERR_UNSUPPORTED
+    assert call(D=256, ldo=256) == mx.MX_ERR_UNSUPPORTED
+    assert call(fp_=mx.fmt(16, 8, block_rows=2), fv=mx.fmt(16, 8, block_rows=2)) == mx.MX_ERR_UNSUPPORTED
+    assert call(Sq=0) == mx.MX_OK
+    torch.cuda.synchronize()
