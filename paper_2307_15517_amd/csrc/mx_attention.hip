@@ -69,6 +69,11 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// The value is computed before this point of the program: an empty volatile statement is ordered with the
+// scheduling fences, and so, through it, is the (otherwise freely movable) arithmetic that produces v.
+__device__ __forceinline__ void pin(float v) { asm volatile("" ::"v"(v)); }
+__device__ __forceinline__ void pin(int v) { asm volatile("" ::"v"(v)); }
+
 constexpr int kAttnStages = 4;
 constexpr int kAttnRQ = 2;         // query tiles of 32 per wave
 
@@ -94,16 +99,23 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
     const uint32_t lane16 = lane * 16;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smem;
 
-    // the wave's Q fragments (right operand of S^T = K Q^T): lane 32h + i holds query i, elements 8h..8h+7
+    // the wave's Q fragments (right operand of S^T = K Q^T): lane 32h + i holds query i, elements 8h..8h+7.
+    // A negative scale is carried by the operand (sign bits flipped: every product and sum changes
+    // sign exactly), so that below the largest score is the largest argument of exp.
     const int64_t qt0 = (bq * 4 + wave) * RQ;
+    const int flip = g.c < 0.f ? (int)0x80008000u : 0;
+    const float c = __builtin_fabsf(g.c);
     v4i qf[RQ][NK];
 #pragma unroll
     for (int q = 0; q < RQ; ++q) {
         int64_t rt = qt0 + q;
         rt = rt < g.q_tiles ? rt : g.q_tiles - 1;       // tiles past the matrix re-read its last tile (never stored)
 #pragma unroll
-        for (int kk = 0; kk < NK; ++kk)
+        for (int kk = 0; kk < NK; ++kk) {
             qf[q][kk] = *reinterpret_cast<const v4i*>(Qbase + (rt * KS + (kk >> 1)) * kBfUnitBytes + (kk & 1) * 1024 + lane16);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) qf[q][kk][d] ^= flip;
+        }
     }
 
     // K rows are read permuted (bits 2 and 3 of the row swapped): result register r of lane 32h + i is
@@ -123,6 +135,11 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[dt][q][r] = 0.f;
     const float qmax = (float)((1 << (g.wp - 1)) - 1);
+    const int wm2 = g.wp - 2;
+
+    // scores of two consecutive key tiles live in two register sets: while the arithmetic on one tile's
+    // scores runs on the vector units, the matrix cores take the next tile's.
+    v16f s[2][RQ];
 
     auto sweep = [&](auto pvc) {
         constexpr bool PV = decltype(pvc)::value;
@@ -152,105 +169,194 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
 #pragma unroll
             for (int q = 0; q < NL; ++q) copy16_to_lds(src[q] + kt * adv[q], lane16, lds0 + stage * STAGE + dst[q]);
         };
-#pragma unroll
-        for (int st = 0; st < S - 1; ++st) issue(st, st);
-        int cur = 0;
-        for (int64_t kt = 0; kt < g.nt; ++kt) {
-            // copies in flight, oldest first: tiles kt .. kt+S-2.  Tile kt has landed once only the newest
-            // S-2 tiles' copies are outstanding; the barrier publishes it and tells that every wave is done
-            // with the stage of tile kt-1, which the copy of tile kt+S-1 overwrites.
-            wait_vmcnt<(S - 2) * NL>();
-            __syncthreads();
-            issue(kt + S - 1, cur == 0 ? S - 1 : cur - 1);
-            const uint8_t* st = smem + cur * STAGE;
-            cur = cur + 1 == S ? 0 : cur + 1;
-
-            v4i kf[NK];
+        // S^T of the key tile in `stage` into register set `set`: fragments first, then matrix instruction
+        // m = 0 .. 2*NK-1 one at a time (the caller slots vector work between them)
+        v4i kf[NK];
+        auto read_k = [&](int stage) {
+            const uint8_t* st = smem + stage * STAGE;
 #pragma unroll
             for (int kk = 0; kk < NK; ++kk)
                 kf[kk] = *reinterpret_cast<const v4i*>(st + (kk >> 1) * kBfUnitBytes + (kk & 1) * 1024 + koff);
-            v16f s[RQ];
+        };
+        auto score_mfma = [&](int m, auto setc) {
+            constexpr int set = decltype(setc)::value;
+            const int kk = m / RQ, q = m % RQ;              // consecutive instructions never share an accumulator
+            v16f zero;
 #pragma unroll
-            for (int q = 0; q < RQ; ++q)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[q][r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < NK; ++kk)
-#pragma unroll
-                for (int q = 0; q < RQ; ++q)
-                    s[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, kf[kk]),
-                                                                   __builtin_bit_cast(v8bf, qf[q][kk]), s[q], 0, 0, 0);
-            const bool ragged = (kt + 1) * 32 > g.Sk;   // keys past the end take no part (uniform branch)
-            const int64_t key0 = kt * 32 + 8 * h;
-            if constexpr (!PV) {
-#pragma unroll
-                for (int q = 0; q < RQ; ++q) {
-                    float t[16];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) t[r] = s[q][r] * g.c;
-                    if (ragged) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (key0 + 16 * (r >> 3) + (r & 7) >= g.Sk) t[r] = -__builtin_inff();
-                    }
-                    float tm = t[0];
-#pragma unroll
-                    for (int r = 1; r < 16; ++r) tm = __builtin_fmaxf(tm, t[r]);
-                    const float m_new = __builtin_fmaxf(m_run[q], tm);
-                    const float m_use = m_new == -__builtin_inff() ? 0.f : m_new;
-                    float sum = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(t[r] - m_use);
-                    l_run[q] = l_run[q] * __builtin_amdgcn_exp2f(m_run[q] - m_use) + sum;
-                    m_run[q] = m_new;
-                }
-            } else {
-                v4i vf[DT][2];
+            for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+            s[set][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, kf[kk]), __builtin_bit_cast(v8bf, qf[q][kk]),
+                                                                kk == 0 ? zero : s[set][q], 0, 0, 0);
+        };
+        // One key tile: tile kt's scores are in set kt % 2, tile kt+1's are started into the other set.
+        // RAG: keys past Sk are masked (only the last tile can have them).
+        // The instruction order is written out and pinned: one matrix instruction, then its share of the
+        // vector work (given as numbered units), so that both pipes stay busy with one wave per SIMD.
+        auto body = [&](int64_t kt, int cur, auto setc, auto ragc) {
+            constexpr int set = decltype(setc)::value;
+            constexpr bool RAG = decltype(ragc)::value;
+            const auto nset = std::integral_constant<int, set ^ 1>{};
+            const int nxt = cur + 1 == S ? 0 : cur + 1;
+            const uint8_t* st = smem + cur * STAGE;
+            v4i vf[PV ? DT : 1][2];
+            if constexpr (PV) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                     for (int b = 0; b < 2; ++b)
                         vf[dt][b] = *reinterpret_cast<const v4i*>(st + (KS + dt) * kBfUnitBytes + b * 1024 + lane16);
-#pragma unroll
-                for (int q = 0; q < RQ; ++q) {
-#pragma unroll
-                    for (int b = 0; b < 2; ++b) {
-                        // one block of 16 keys of query i: this lane's half, quantized with the arithmetic of mx_quantize
-                        float p[8];
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[q][8 * b + e], g.c, -mrow[q]));
-                        if (ragged) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (key0 + 16 * b + e >= g.Sk) p[e] = 0.f;
-                        }
-                        float am = p[0];
-#pragma unroll
-                        for (int e = 1; e < 8; ++e) am = __builtin_fmaxf(am, p[e]);
-                        am = __builtin_fmaxf(am, __shfl_xor(am, 32, 64));
-                        const int ef = (int)(__float_as_uint(am) >> 23);
-                        int E = ef == 0 ? -127 : ef - 127;
-                        E = E < -g.bias_p ? -g.bias_p : E;
-                        E = E > g.emax_p ? g.emax_p : E;
-                        const int sh = (g.wp - 2) - E;
-                        uint32_t out[4] = {0, 0, 0, 0};
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const float sc = __builtin_ldexpf(p[e], sh);
-                            float r = RND == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
-                            r = __builtin_fminf(r, qmax);                      // probabilities are not negative
-                            out[e >> 1] |= bf16_of(r, -sh) << (16 * (e & 1));
-                        }
-                        v4i pf;
-                        pf[0] = (int)out[0]; pf[1] = (int)out[1]; pf[2] = (int)out[2]; pf[3] = (int)out[3];
-#pragma unroll
-                        for (int dt = 0; dt < DT; ++dt)
-                            o[dt][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vf[dt][b]),
-                                                                               __builtin_bit_cast(v8bf, pf), o[dt][q], 0, 0, 0);
-                    }
-                }
             }
+            // copies in flight, oldest first: tiles kt+1 .. kt+S-1.  Tile kt+1 has landed once only the newest
+            // S-2 tiles' copies are outstanding; the barrier publishes it and tells that every wave has taken
+            // what it needs of tile kt's stage, which the copy of tile kt+S overwrites.
+            wait_vmcnt<(S - 2) * NL>();
+            __syncthreads();
+            issue(kt + S, cur);
+            read_k(nxt);
+            const int valid = (int)(g.Sk - kt * 32) - 8 * h;   // this lane's key 16*b + e is real iff 16*b + e < valid
+            auto masked = [&](int r) { return RAG && 16 * (r >> 3) + (r & 7) >= valid; };
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (!PV) {
+                // units of one query tile: 0 = tile maximum and the new running maximum, 1..4 = four
+                // exponentials each, 5 = the running sum
+                constexpr int NU = 6;
+                float m_old[RQ], m_use[RQ], sum[RQ];
+                auto unit = [&](int q, int u) {
+                    if (u == 0) {
+                        float sm = -__builtin_inff();
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) sm = __builtin_fmaxf(sm, masked(r) ? -__builtin_inff() : s[set][q][r]);
+                        m_old[q] = m_run[q];
+                        m_run[q] = __builtin_fmaxf(m_run[q], sm * c);
+                        m_use[q] = m_run[q] == -__builtin_inff() ? 0.f : m_run[q];
+                        sum[q] = 0.f;
+                        pin(m_use[q]);
+                    } else if (u < 5) {
+#pragma unroll
+                        for (int r = 4 * (u - 1); r < 4 * u; ++r) {
+                            float arg = __builtin_fmaf(s[set][q][r], c, -m_use[q]);
+                            if (masked(r)) arg = -__builtin_inff();   // also when c is 0
+                            sum[q] += __builtin_amdgcn_exp2f(arg);
+                        }
+                        pin(sum[q]);
+                    } else {
+                        l_run[q] = l_run[q] * __builtin_amdgcn_exp2f(m_old[q] - m_use[q]) + sum[q];
+                        pin(l_run[q]);
+                    }
+                };
+                constexpr int NM = RQ * NK;
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    score_mfma(m, nset);
+#pragma unroll
+                    for (int x = m * (RQ * NU) / NM; x < (m + 1) * (RQ * NU) / NM; ++x) unit(x / NU, x % NU);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                // One query tile = two blocks of 16 keys, this lane's half of each.  a = log2 of the
+                // probability; the block exponent is the integer part of the largest a (the quantizer's
+                // floor(log2 max)), the mantissas are round(2^(a - E + w - 2)): the arithmetic of mx_quantize
+                // on P.  Units: 0..3 = four a each, 4 = half-block maxima and their exchange, 5 = nothing (the
+                // exchange is in flight), 6 = exponents, 7..22 = one element each, 23, 24 = operand registers.
+                static_assert(RQ == 2, "the order below is written for two query tiles per wave");
+                constexpr int NU = 25;
+                float a[RQ][16], el[RQ][16], am[RQ][2], mo[RQ][2], shf[RQ][2];
+                int sh[RQ][2];
+                v4i pf[RQ][2];
+                auto unit = [&](int q, int u) {
+                    if (u < 4) {
+#pragma unroll
+                        for (int r = 4 * u; r < 4 * u + 4; ++r) {
+                            a[q][r] = __builtin_fmaf(s[set][q][r], c, -mrow[q]);
+                            if (masked(r)) a[q][r] = -__builtin_inff();
+                            pin(a[q][r]);
+                        }
+                    } else if (u == 4) {
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            float m = a[q][8 * b];
+#pragma unroll
+                            for (int e = 1; e < 8; ++e) m = __builtin_fmaxf(m, a[q][8 * b + e]);
+                            am[q][b] = m;
+                            mo[q][b] = __shfl_xor(m, 32, 64);
+                        }
+                    } else if (u == 5) {
+                    } else if (u == 6) {
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            float m = __builtin_fmaxf(am[q][b], mo[q][b]);
+                            m = __builtin_fmaxf(m, -200.f);                   // keeps the conversion below in range
+                            int E = (int)__builtin_floorf(m);
+                            E = E < -g.bias_p ? -g.bias_p : E;
+                            E = E > g.emax_p ? g.emax_p : E;
+                            sh[q][b] = wm2 - E;
+                            shf[q][b] = (float)sh[q][b];
+                            pin(shf[q][b]);
+                        }
+                    } else if (u < 23) {
+                        const int r = u - 7, b = r >> 3;
+                        const float sc = __builtin_amdgcn_exp2f(a[q][r] + shf[q][b]);
+                        float v = RND == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
+                        v = __builtin_fminf(v, qmax);                         // probabilities are not negative
+                        el[q][r] = __builtin_ldexpf(v, -sh[q][b]);            // an exact bfloat16 number
+                        pin(el[q][r]);
+                    } else {
+                        const int b = u - 23;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d)                           // the upper halves of two fp32 values
+                            pf[q][b][d] = (int)__builtin_amdgcn_perm(__float_as_uint(el[q][8 * b + 2 * d + 1]),
+                                                                     __float_as_uint(el[q][8 * b + 2 * d]), 0x07060302u);
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) pin(pf[q][b][d]);
+                    }
+                };
+                auto out_mfma = [&](int q, int m) {
+                    const int b = m / DT, dt = m % DT;
+                    o[dt][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vf[dt][b]),
+                                                                       __builtin_bit_cast(v8bf, pf[q][b]), o[dt][q], 0, 0, 0);
+                };
+                // the next tile's scores under the vector work of the first query tile ...
+                constexpr int NM = RQ * NK;
+                unit(0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    score_mfma(m, nset);
+#pragma unroll
+                    for (int x = 1 + m * (NU - 1) / NM; x < 1 + (m + 1) * (NU - 1) / NM; ++x) unit(0, x);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // ... the first query tile's second product under the vector work of the second ...
+#pragma unroll
+                for (int m = 0; m < 2 * DT; ++m) {
+                    out_mfma(0, m);
+#pragma unroll
+                    for (int x = m * NU / (2 * DT); x < (m + 1) * NU / (2 * DT); ++x) unit(1, x);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // ... and the second query tile's second product
+#pragma unroll
+                for (int m = 0; m < 2 * DT; ++m) out_mfma(1, m);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+
+#pragma unroll
+        for (int st = 0; st < S; ++st) issue(st, st);
+        wait_vmcnt<(S - 1) * NL>();
+        __syncthreads();
+        read_k(0);
+#pragma unroll
+        for (int m = 0; m < RQ * NK; ++m) score_mfma(m, std::integral_constant<int, 0>{});
+        // tiles in pairs (the register sets alternate); the last one or two tiles take the masking form
+        int64_t kt = 0;
+        int cur = 0;
+        auto advance = [&]() { cur = cur + 1 == S ? 0 : cur + 1; ++kt; };
+        while (kt + 2 < g.nt) {
+            body(kt, cur, std::integral_constant<int, 0>{}, std::false_type{}); advance();
+            body(kt, cur, std::integral_constant<int, 1>{}, std::false_type{}); advance();
         }
+        body(kt, cur, std::integral_constant<int, 0>{}, std::true_type{}); advance();
+        if (kt < g.nt) { body(kt, cur, std::integral_constant<int, 1>{}, std::true_type{}); advance(); }
         wait_vmcnt<0>();                                  // the clamped tail copies must not outlive the stage's next use
         __syncthreads();
     };
@@ -269,26 +375,32 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
 
     // O^T registers: register r of lane 32h + i is element 8*(r/4) + 4h + r%4 of the tile's 32, query i
     float* O = g.O + bz * g.o_batch_stride;
+    auto store = [&](auto vecc) {
+        constexpr bool VEC = decltype(vecc)::value;
 #pragma unroll
-    for (int q = 0; q < RQ; ++q) {
-        const int64_t row = (qt0 + q) * 32 + i;
-        if (row >= g.Sq) continue;
+        for (int q = 0; q < RQ; ++q) {
+            const int64_t row = (qt0 + q) * 32 + i;
+            if (row < g.Sq) {
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+                for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const int64_t d = dt * 32 + 8 * gq + 4 * h;
-                if (d >= g.D) continue;                   // D is a multiple of 16: four elements or none
-                float* dst = O + row * g.ldo + d;
-                if (g.vec) {
-                    *reinterpret_cast<float4*>(dst) = make_float4(o[dt][q][4 * gq], o[dt][q][4 * gq + 1],
-                                                                  o[dt][q][4 * gq + 2], o[dt][q][4 * gq + 3]);
-                } else {
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const int d = dt * 32 + 8 * gq + 4 * h;
+                        if (d < (int)g.D) {                  // D is a multiple of 16: four elements or none
+                            float* dst = O + row * g.ldo + d;
+                            if constexpr (VEC) {
+                                *reinterpret_cast<float4*>(dst) = make_float4(o[dt][q][4 * gq], o[dt][q][4 * gq + 1],
+                                                                              o[dt][q][4 * gq + 2], o[dt][q][4 * gq + 3]);
+                            } else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) dst[j] = o[dt][q][4 * gq + j];
-                }
+                                for (int j = 0; j < 4; ++j) dst[j] = o[dt][q][4 * gq + j];
+                            }
+                        }
+                    }
             }
-    }
+        }
+    };
+    if (g.vec) store(std::true_type{}); else store(std::false_type{});
 }
 
 template <int KS, int DT>
