@@ -252,55 +252,47 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
                     __builtin_amdgcn_sched_barrier(0);
                 }
             } else {
-                // One query tile = two blocks of 16 keys, this lane's half of each.  a = log2 of the
-                // probability; the block exponent is the integer part of the largest a (the quantizer's
-                // floor(log2 max)), the mantissas are round(2^(a - E + w - 2)): the arithmetic of mx_quantize
-                // on P.  Units: 0..3 = four a each, 4 = half-block maxima and their exchange, 5 = nothing (the
-                // exchange is in flight), 6 = exponents, 7..22 = one element each, 23, 24 = operand registers.
+                // One query tile = two blocks of 16 keys, this lane's half of each.  With a = log2 of the
+                // probability, the block exponent is the integer part of the largest a (the quantizer's
+                // floor(log2 max)) and the mantissas are round(2^(a - E + w - 2)): the arithmetic of mx_quantize
+                // on P.  exp2 grows with the score, so the maximum is taken over the scores themselves.
+                // Units: 0 = half-block maxima, their exchange with the other lane half, the exponents;
+                // 1..16 = one element each; 17, 18 = operand registers.
                 static_assert(RQ == 2, "the order below is written for two query tiles per wave");
-                constexpr int NU = 25;
-                float a[RQ][16], el[RQ][16], am[RQ][2], mo[RQ][2], shf[RQ][2];
+                constexpr int NU = 19;
+                float el[RQ][16], off[RQ][2];
                 int sh[RQ][2];
                 v4i pf[RQ][2];
                 auto unit = [&](int q, int u) {
-                    if (u < 4) {
-#pragma unroll
-                        for (int r = 4 * u; r < 4 * u + 4; ++r) {
-                            a[q][r] = __builtin_fmaf(s[set][q][r], c, -mrow[q]);
-                            if (masked(r)) a[q][r] = -__builtin_inff();
-                            pin(a[q][r]);
-                        }
-                    } else if (u == 4) {
+                    if (u == 0) {
 #pragma unroll
                         for (int b = 0; b < 2; ++b) {
-                            float m = a[q][8 * b];
+                            float sm = -__builtin_inff();
 #pragma unroll
-                            for (int e = 1; e < 8; ++e) m = __builtin_fmaxf(m, a[q][8 * b + e]);
-                            am[q][b] = m;
-                            mo[q][b] = __shfl_xor(m, 32, 64);
-                        }
-                    } else if (u == 5) {
-                    } else if (u == 6) {
-#pragma unroll
-                        for (int b = 0; b < 2; ++b) {
-                            float m = __builtin_fmaxf(am[q][b], mo[q][b]);
-                            m = __builtin_fmaxf(m, -200.f);                   // keeps the conversion below in range
+                            for (int e = 0; e < 8; ++e) sm = __builtin_fmaxf(sm, masked(8 * b + e) ? -__builtin_inff() : s[set][q][8 * b + e]);
+                            // both lane halves get the larger of the two halves' values
+                            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(sm), __float_as_uint(sm), false, false);
+                            sm = __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                            float m = __builtin_fmaf(sm, c, -mrow[q]);
+                            m = __builtin_fmaxf(m, -200.f);                   // also for all keys masked, or c = 0 with them
                             int E = (int)__builtin_floorf(m);
                             E = E < -g.bias_p ? -g.bias_p : E;
                             E = E > g.emax_p ? g.emax_p : E;
                             sh[q][b] = wm2 - E;
-                            shf[q][b] = (float)sh[q][b];
-                            pin(shf[q][b]);
+                            off[q][b] = (float)sh[q][b] - mrow[q];
+                            pin(off[q][b]);
                         }
-                    } else if (u < 23) {
-                        const int r = u - 7, b = r >> 3;
-                        const float sc = __builtin_amdgcn_exp2f(a[q][r] + shf[q][b]);
+                    } else if (u < 17) {
+                        const int r = u - 1, b = r >> 3;
+                        float arg = __builtin_fmaf(s[set][q][r], c, off[q][b]);
+                        if (masked(r)) arg = -__builtin_inff();
+                        const float sc = __builtin_amdgcn_exp2f(arg);
                         float v = RND == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
                         v = __builtin_fminf(v, qmax);                         // probabilities are not negative
                         el[q][r] = __builtin_ldexpf(v, -sh[q][b]);            // an exact bfloat16 number
                         pin(el[q][r]);
                     } else {
-                        const int b = u - 23;
+                        const int b = u - 17;
 #pragma unroll
                         for (int d = 0; d < 4; ++d)                           // the upper halves of two fp32 values
                             pf[q][b][d] = (int)__builtin_amdgcn_perm(__float_as_uint(el[q][8 * b + 2 * d + 1]),
