@@ -521,6 +521,21 @@ def test_gemm_is_deterministic():
     assert torch.equal(y1, y2)
 
 
+def oracle_probabilities(Q, K, block, wq, wk, dim):
+    """fp32 probabilities [heads, Sq, Sk] for the second product of the unfused attention tests, from the
+    oracle's scores (float64 softmax, held as fp32): an input of both sides that owes nothing to the kernels."""
+    out = np.empty((Q.shape[0], Q.shape[1], K.shape[1]), np.float32)
+    for hd in range(Q.shape[0]):
+        oq, oqe = orc.quantize(Q[hd], block, wq)
+        ok, oke = orc.quantize(K[hd], block, wk)
+        z = orc.gemm(oq, oqe, wq, ok, oke, wk, block) / np.sqrt(dim)
+        z -= z.max(axis=1, keepdims=True)
+        np.exp(z, out=z)
+        z /= z.sum(axis=1, keepdims=True)
+        out[hd] = z
+    return out
+
+
 @pytest.mark.parametrize("seed", [0, 3])
 def test_attention_shaped_products_mixed_widths(seed):
     """Reduced form of the mixed-precision attention workload: per head Q K^T (blocks of 16 along the head
@@ -538,7 +553,8 @@ def test_attention_shaped_products_mixed_widths(seed):
     B = mx.pack(km, ke, heads, seq, dim, fk)
     S = mx.gemm(A, fq, B, fk, seq, seq, dim, batch=heads)
     torch.cuda.synchronize()
-    P = torch.softmax(S / np.sqrt(dim), dim=-1).contiguous()          # fp32, outside the MXInt path
+    Ph = oracle_probabilities(Q, K, block, wq, wk, dim)               # fp32, outside the MXInt path
+    P = dev(Ph)
     # out = P V: P blocked along its rows' sequence axis, V along the sequence (its strided axis)
     pm, pe = mx.quantize(P, fp_)
     vm, ve = mx.quantize(dev(V), fv, axis=0)                          # canonical form of V^T: [heads, dim, seq]
@@ -546,7 +562,6 @@ def test_attention_shaped_products_mixed_widths(seed):
     B2 = mx.pack(vm, ve, heads, dim, seq, fv)
     O = mx.gemm(A2, fp_, B2, fv, seq, dim, seq, batch=heads)
     torch.cuda.synchronize()
-    Ph = host(P)
     for hd in range(heads):
         oq, oqe = orc.quantize(Q[hd], block, wq)
         ok, oke = orc.quantize(K[hd], block, wk)
@@ -593,8 +608,8 @@ def test_attention_full_size_sampled_heads_and_rows():
     A = mx.quantize_pack(dev(Q), fq)
     B = mx.quantize_pack(dev(K), fk)
     S = mx.gemm(A, fq, B, fk, seq, seq, dim, batch=heads)
-    P = torch.softmax(S / np.sqrt(dim), dim=-1).contiguous()
-    A2 = mx.quantize_pack(P, fp_)
+    Ph = oracle_probabilities(Q, K, block, wq, wk, dim)
+    A2 = mx.quantize_pack(dev(Ph), fp_)
     vm, ve = mx.quantize(dev(V), fv, axis=0)
     B2 = mx.pack(vm, ve, heads, dim, seq, fv)
     O = mx.gemm(A2, fp_, B2, fv, seq, dim, seq, batch=heads)
@@ -605,7 +620,7 @@ def test_attention_full_size_sampled_heads_and_rows():
         ok, oke = orc.quantize(K[hd], block, wk)
         s_ref, s_mag = orc.gemm(oq, oqe, wq, ok, oke, wk, block, rows=(r0, r1), want_mag=True)
         say("scores head", hd, "worst", check_product(host(S[hd, r0:r1]), s_ref[r0:r1], s_mag[r0:r1], "scores"))
-        op, ope = orc.quantize(host(P[hd]), block, wp)
+        op, ope = orc.quantize(Ph[hd], block, wp)
         ov, ove = orc.quantize(V[hd], block, wv, axis=0)
         o_ref, o_mag = orc.gemm(op, ope, wp, ov, ove, wv, block, rows=(r0, r1), want_mag=True)
         say("output head", hd, "worst", check_product(host(O[hd, r0:r1]), o_ref[r0:r1], o_mag[r0:r1], "output"))
@@ -759,8 +774,8 @@ def test_matrix_attention_full_size_sampled_heads_and_rows():
     A = mx.quantize_pack(dev(Q), fq, MAT)
     B = mx.quantize_pack(dev(K), fk, MAT)
     S = mx.gemm(A, fq, B, fk, seq, seq, dim, batch=heads, layout=MAT)
-    P = torch.softmax(S / np.sqrt(dim), dim=-1).contiguous()
-    A2 = mx.quantize_pack(P, fp_, MAT)
+    Ph = oracle_probabilities(Q, K, block, wq, wk, dim)
+    A2 = mx.quantize_pack(dev(Ph), fp_, MAT)
     vm, ve = mx.quantize(dev(V), fv, axis=0)
     B2 = mx.pack(vm, ve, heads, dim, seq, fv, MAT)
     O = mx.gemm(A2, fp_, B2, fv, seq, dim, seq, batch=heads, layout=MAT)
@@ -771,7 +786,7 @@ def test_matrix_attention_full_size_sampled_heads_and_rows():
         ok, oke = orc.quantize(K[hd], block, wk)
         s_ref, s_mag = orc.gemm(oq, oqe, wq, ok, oke, wk, block, rows=(r0, r1), want_mag=True)
         say("scores head", hd, "worst", check_product(host(S[hd, r0:r1]), s_ref[r0:r1], s_mag[r0:r1], "scores"))
-        op, ope = orc.quantize(host(P[hd]), block, wp)
+        op, ope = orc.quantize(Ph[hd], block, wp)
         ov, ove = orc.quantize(V[hd], block, wv, axis=0)
         o_ref, o_mag = orc.gemm(op, ope, wp, ov, ove, wv, block, rows=(r0, r1), want_mag=True)
         say("output head", hd, "worst", check_product(host(O[hd, r0:r1]), o_ref[r0:r1], o_mag[r0:r1], "output"))
