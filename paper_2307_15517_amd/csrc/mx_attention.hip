@@ -19,9 +19,10 @@
 // v_mfma_f32_32x32x16_bf16 for O^T = V^T P^T.  The block maximum is completed with the lane of the
 // other half (one exchange per block).
 //
-// Work split: a workgroup of four waves owns 256 queries of one head (a wave: two tiles of 32, its
-// Q fragments stay in registers); the K (and in sweep 2 the V^T) units of one tile of 32 keys are
-// copied global -> LDS with 16-byte direct-to-LDS loads, four stages, one barrier per key tile.
+// Work split: a workgroup of four waves owns 128 queries of one head (a wave: one tile of 32, its
+// Q fragments stay in registers), two workgroups per compute unit; the K (and in sweep 2 the V^T)
+// units of one tile of 32 keys are copied global -> LDS with 16-byte direct-to-LDS loads, four
+// stages, one barrier per key tile.
 #include <type_traits>
 
 #include "mx_bf16.h"
@@ -75,12 +76,17 @@ __device__ __forceinline__ void pin(float v) { asm volatile("" ::"v"(v)); }
 __device__ __forceinline__ void pin(int v) { asm volatile("" ::"v"(v)); }
 
 constexpr int kAttnStages = 4;
-constexpr int kAttnRQ = 2;         // query tiles of 32 per wave
+// Query tiles of 32 per wave.  1: 205 registers, two workgroups per compute unit, accumulators in ordinary
+// registers (123 us at 32 x 2048 x 2048 x 128); 2: 363 registers, one workgroup, half the LDS reads per matrix
+// instruction but every score copied out of the accumulation registers (128 us).
+constexpr int kAttnRQ = 1;
 
-// KS: K steps of 32 along the head dimension (2 or 4); DT: tiles of 32 along the head dimension of V.
-template <int KS, int DT, int RND>
-__global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
-    constexpr int RQ = kAttnRQ, S = kAttnStages;
+// KS: K steps of 32 along the head dimension (2 or 4); DT: tiles of 32 along the head dimension of V;
+// RQ: query tiles of 32 per wave.  RQ = 2 needs more than 256 registers (one wave per SIMD); RQ = 1 leaves
+// room for two workgroups per compute unit, whose waves fill each other's waits.
+template <int KS, int DT, int RND, int RQ>
+__global__ __launch_bounds__(256, RQ == 1 ? 2 : 1) void attention_bf16_kernel(AttnArgs g) {
+    constexpr int S = kAttnStages;
     constexpr int NK = 2 * KS;                          // matrix instructions (16 elements) along the head dimension
     constexpr int STAGE = (KS + DT) * kBfUnitBytes;     // K units, then V^T units
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -257,8 +263,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
                 // floor(log2 max)) and the mantissas are round(2^(a - E + w - 2)): the arithmetic of mx_quantize
                 // on P.  exp2 grows with the score, so the maximum is taken over the scores themselves.
                 // Units: 0 = half-block maxima, their exchange with the other lane half, the exponents;
-                // 1..16 = one element each; 17, 18 = operand registers.
-                static_assert(RQ == 2, "the order below is written for two query tiles per wave");
+                // 1..16 = one element each; 17, 18 = operand registers.  (Taking the elements four at a time,
+                // operation by operation, measured slower: the exponentials then queue behind each other.)
                 constexpr int NU = 19;
                 float el[RQ][16], off[RQ][2];
                 int sh[RQ][2];
@@ -306,7 +312,8 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
                     o[dt][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, vf[dt][b]),
                                                                        __builtin_bit_cast(v8bf, pf[q][b]), o[dt][q], 0, 0, 0);
                 };
-                // the next tile's scores under the vector work of the first query tile ...
+                // the next tile's scores under the vector work of the first query tile, every query tile's
+                // second product under the vector work of the following one, the last one's bare
                 constexpr int NM = RQ * NK;
                 unit(0, 0);
                 __builtin_amdgcn_sched_barrier(0);
@@ -317,17 +324,17 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
                     for (int x = 1 + m * (NU - 1) / NM; x < 1 + (m + 1) * (NU - 1) / NM; ++x) unit(0, x);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                // ... the first query tile's second product under the vector work of the second ...
 #pragma unroll
-                for (int m = 0; m < 2 * DT; ++m) {
-                    out_mfma(0, m);
+                for (int q = 1; q < RQ; ++q)
 #pragma unroll
-                    for (int x = m * NU / (2 * DT); x < (m + 1) * NU / (2 * DT); ++x) unit(1, x);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                // ... and the second query tile's second product
+                    for (int m = 0; m < 2 * DT; ++m) {
+                        out_mfma(q - 1, m);
 #pragma unroll
-                for (int m = 0; m < 2 * DT; ++m) out_mfma(1, m);
+                        for (int x = m * NU / (2 * DT); x < (m + 1) * NU / (2 * DT); ++x) unit(q, x);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                for (int m = 0; m < 2 * DT; ++m) out_mfma(RQ - 1, m);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -395,12 +402,12 @@ __global__ __launch_bounds__(256) void attention_bf16_kernel(AttnArgs g) {
     if (g.vec) store(std::true_type{}); else store(std::false_type{});
 }
 
-template <int KS, int DT>
-mx_status launch_attention(const AttnArgs& g, int rnd, hipStream_t st) {
+template <int KS, int DT, int RQ>
+mx_status launch_attention(AttnArgs& g, int64_t batch, int rnd, hipStream_t st) {
     constexpr int smem = kAttnStages * (KS + DT) * kBfUnitBytes;
-    static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
-    auto k0 = attention_bf16_kernel<KS, DT, MX_RNE>;
-    auto k1 = attention_bf16_kernel<KS, DT, MX_RTZ>;
+    static_assert(smem * (RQ == 1 ? 2 : 1) <= 160 * 1024, "LDS budget of one compute unit");
+    auto k0 = attention_bf16_kernel<KS, DT, MX_RNE, RQ>;
+    auto k1 = attention_bf16_kernel<KS, DT, MX_RTZ, RQ>;
     static bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute((const void*)k0, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess ||
@@ -408,11 +415,18 @@ mx_status launch_attention(const AttnArgs& g, int rnd, hipStream_t st) {
             return MX_ERR_DEVICE;
         configured = true;
     }
+    g.tiles_q = ceil_div(g.Sq, 128 * RQ);
+    g.total = g.tiles_q * batch;
     if (g.total > 0x7fffff00LL) return MX_ERR_UNSUPPORTED;
     dim3 grid((unsigned)(ceil_div(g.total, 8) * 8));
     hipLaunchKernelGGL(rnd == MX_RNE ? k0 : k1, grid, dim3(256), smem, st, g);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
+}
+
+template <int KS, int DT>
+mx_status launch_attention_rq(AttnArgs& g, int64_t batch, int rnd, hipStream_t st) {
+    return launch_attention<KS, DT, kAttnRQ>(g, batch, rnd, st);
 }
 
 }  // namespace
@@ -451,14 +465,14 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
     g.matrixQ = gq.matrix; g.matrixK = gk.matrix; g.matrixV = gv.matrix;
     g.q_tiles = gq.row_tiles; g.nt = gk.row_tiles; g.v_ksteps = gv.ksteps;
     g.ldo = ldo; g.o_batch_stride = o_batch_stride;
-    g.tiles_q = ceil_div(Sq, 128 * kAttnRQ);
-    g.total = g.tiles_q * batch;
+    g.tiles_q = g.total = 0;
     g.c = scale * 1.4426950408889634f;
     g.wp = fp.mant_bits; g.bias_p = (1 << (fp.exp_bits - 1)) - 1;
     g.emax_p = ((1 << fp.exp_bits) - 1) - g.bias_p;
     g.vec = (((uintptr_t)O & 15) == 0 && ldo % 4 == 0 && o_batch_stride % 4 == 0) ? 1 : 0;
     const int dt = (int)ceil_div(D, 32);
     hipStream_t st = (hipStream_t)stream;
-    if (gq.ksteps == 2) return dt == 1 ? launch_attention<2, 1>(g, fp.rounding, st) : launch_attention<2, 2>(g, fp.rounding, st);
-    return dt == 3 ? launch_attention<4, 3>(g, fp.rounding, st) : launch_attention<4, 4>(g, fp.rounding, st);
+    if (gq.ksteps == 2)
+        return dt == 1 ? launch_attention_rq<2, 1>(g, batch, fp.rounding, st) : launch_attention_rq<2, 2>(g, batch, fp.rounding, st);
+    return dt == 3 ? launch_attention_rq<4, 3>(g, batch, fp.rounding, st) : launch_attention_rq<4, 4>(g, batch, fp.rounding, st);
 }
