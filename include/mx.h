@@ -18,7 +18,7 @@
  *   - The return value is an mx_status.  Nothing throws or aborts across this
  *     boundary.  MX_ERR_BAD_ARG: a null pointer, a negative size, a size that is not
  *     a whole number of blocks, a format outside the ranges stated at mx_format, or
- *     a misaligned pointer.  MX_ERR_UNSUPPORTED: a legal request this build has no
+ *     a misaligned pointer.  MX_ERR_UNSUPPORTED: a legal request this library has no
  *     kernel for.  MX_ERR_DEVICE: the HIP runtime refused the launch.
  *   - Inputs must be finite; NaN and infinity give unspecified mantissas (no fault).
  *

@@ -422,6 +422,34 @@ def test_linear_equals_quantize_pack_gemm(M):
     torch.cuda.synchronize()
     assert torch.equal(y1, y2)            # same arithmetic in the same order: identical bits
 
+@pytest.mark.parametrize("block,wx,ww,M,e,rounding", [(16, 5, 4, 5, 8, mx.MX_RNE), (32, 2, 8, 8, 8, mx.MX_RTZ),
+                                                       (64, 8, 3, 3, 5, mx.MX_RNE), (16, 7, 6, 4, 4, mx.MX_RTZ)])
+def test_linear_rows_3_to_8_formats_and_alignment(block, wx, ww, M, e, rounding):
+    """mx_linear for 3..8 rows over block sizes, widths, narrow exponents and truncation, with K not a whole
+    number of chunks: identical bits to quantize + pack + product, for rows that are 16-byte aligned and
+    rows that are not."""
+    rng = np.random.default_rng(block * 100 + wx)
+    K, N = 7 * block, 100
+    xpad = (rng.standard_normal((M, K + 4)) * np.exp2(rng.integers(-6, 7, size=(M, 1)))).astype(np.float32)
+    wt = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    fa, fb = mx.fmt(block, wx, e, rounding), mx.fmt(block, ww, e, rounding)
+    bm, be = mx.quantize(dev(wt), fb)
+    B = mx.pack(bm, be, 1, N, K, fb)
+    xd = dev(xpad)
+    scratch = torch.zeros(mx.mx_packed_bytes(1, M, K, fa), dtype=torch.uint8, device=DEV)
+    ys = []
+    for off in (0, 1):                                   # element offset 1: rows not 16-byte aligned
+        xv = xd[:, off:off + K]
+        am, ae = mx.quantize(xv, fa)
+        A = mx.pack(am, ae, 1, M, K, fa)
+        y1 = mx.gemm(A, fa, B, fb, M, N, K)[0]
+        y2 = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV)
+        mx.mx_linear(xv, M, K, K + 4, fa, scratch, B, N, fb, mx.MX_LAYOUT_FRAGMENT, y2, N)
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y2)
+        y_ref, mag = orc.linear(xpad[:, off:off + K], wt, block, wx, ww, e, rounding, want_mag=True)
+        check_product(host(y2), y_ref, mag, "linear block %d off %d" % (block, off))
+
 
 @pytest.mark.parametrize("M,K,block", [(3, 300 * 64, 16), (8, 270 * 128, 32), (1, 64, 16), (2, 5 * 256, 64)])
 def test_gemv_long_and_short_k(M, K, block):
