@@ -323,6 +323,122 @@ int mxo_cast(const int8_t *q, const uint8_t *exps, int64_t rows, int64_t cols, i
     return MXO_OK;
 }
 
+/*
+ * ------------------------------------------------------------------------------------------
+ * The paper's two other block formats (Section 2, "What are MX Formats?"): Block Minifloat
+ * (BMF), whose elements are small floating-point numbers that share the exponent *bias* of
+ * their block, and Block Logarithm (BL), which is BMF without mantissa bits -- every value a
+ * power of two.  The paper gives the idea and no bit-level definition; the reading taken here
+ * (all of it a choice of this implementation):
+ *   - an element is sign | c (e bits) | f (m bits), m = 0 for BL; with cmax = 2^e - 1 and the
+ *     block's shared top exponent T,
+ *         c >= 1:  value = +-2^(c - cmax + T) * (1 + f / 2^m)
+ *         c == 0:  value = +-2^(1 - cmax + T) * (f / 2^m)          (gradual underflow; zero)
+ *     i.e. the shared bias is cmax - T; every code is a finite number;
+ *   - the shared byte stores T + 127, T clamped to [-126, 127]; an all-zero block stores 0;
+ *   - T is the exponent of the block maximum after rounding: floor(log2 amax), plus one when
+ *     amax is at or above the midpoint between the largest value of that binade and the next
+ *     power of two (so that rounding never has to saturate); toward-zero rounding never
+ *     carries, T = floor(log2 amax);
+ *   - an element is rounded to the nearest representable value, a tie to the neighbour whose
+ *     code integer (c << m | f) is even (rounding = 0), or toward zero (rounding = 1); a value
+ *     above the largest representable one (only possible when T was clamped) saturates.
+ * ------------------------------------------------------------------------------------------
+ */
+static int mxo_check_minifloat(int block, int e, int m, int rounding) {
+    if (block < 1 || e < 1 || m < 0 || 1 + e + m > 8) return MXO_BAD_ARG;
+    if (rounding != 0 && rounding != 1) return MXO_BAD_ARG;
+    return MXO_OK;
+}
+
+/* codes: one byte per element (sign << (e+m) | c << m | f); shared: one byte per block. */
+int mxo_quantize_minifloat(const float *x, int64_t rows, int64_t cols, int64_t row_stride, int block,
+                           int e, int m, int rounding, uint8_t *codes, uint8_t *shared) {
+    if (mxo_check_minifloat(block, e, m, rounding) != MXO_OK) return MXO_BAD_ARG;
+    if (rows < 0 || cols < 0 || cols % block != 0) return MXO_BAD_ARG;
+    const int64_t nb = cols / block;
+    const int cmax = (1 << e) - 1;
+    int bad = 0;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t b = 0; b < nb; ++b) {
+            const float *src = x + r * row_stride + b * block;
+            uint8_t *dst = codes + r * cols + b * block;
+            double amax = 0.0;
+            for (int i = 0; i < block; ++i) {
+                if (!isfinite(src[i])) bad = 1;
+                const double a = fabs((double)src[i]);
+                if (a > amax) amax = a;
+            }
+            if (amax == 0.0 || bad) {
+                for (int i = 0; i < block; ++i) dst[i] = 0;
+                shared[r * nb + b] = 0;
+                continue;
+            }
+            int ex;
+            frexp(amax, &ex);                       /* amax = fr * 2^ex, fr in [0.5, 1) */
+            int T = ex - 1;                         /* floor(log2 amax) */
+            if (rounding == 0) {
+                /* midpoint between the binade's largest value (2 - 2^-m) * 2^T and 2^(T+1) */
+                const double mid = ldexp(1.0, T + 1) - ldexp(1.0, T - m - 1);
+                if (amax >= mid) T += 1;
+            }
+            if (T < -126) T = -126;
+            if (T > 127) T = 127;
+            const int L = T - cmax + 1;             /* exponent of the smallest normal binade */
+            for (int i = 0; i < block; ++i) {
+                const double a = fabs((double)src[i]);
+                const int sign = signbit(src[i]) ? 1 : 0;
+                int c = 0, f = 0;
+                if (a > 0.0) {
+                    int ea;
+                    frexp(a, &ea);
+                    int k = ea - 1;
+                    if (k < L) k = L;
+                    const double qv = ldexp(a, m - k);          /* in units of the binade's step: exact */
+                    double lo = floor(qv);
+                    const double rem = qv - lo;
+                    long n = (long)lo;
+                    if (rounding == 0 && rem > 0.0) {
+                        /* code integer of the lower neighbour: its parity decides a tie */
+                        const long c_lo = n >= (1L << m) ? (long)(k - L + 1) : 0;
+                        const long code_lo = (c_lo << m) | (n & ((1L << m) - 1));
+                        if (rem > 0.5 || (rem == 0.5 && (code_lo & 1))) n += 1;
+                    }
+                    if (n == (1L << (m + 1))) { k += 1; n = 1L << m; }     /* carry into the next binade */
+                    if (k > T) { k = T; n = (1L << (m + 1)) - 1; }         /* saturate (clamped T only) */
+                    if (n >= (1L << m)) { c = k - L + 1; f = (int)(n - (1L << m)); }
+                    else { c = 0; f = (int)n; }
+                }
+                dst[i] = (uint8_t)((sign << (e + m)) | (c << m) | f);
+            }
+            shared[r * nb + b] = (uint8_t)(T + 127);
+        }
+    }
+    return bad ? MXO_NONFINITE : MXO_OK;
+}
+
+int mxo_dequantize_minifloat(const uint8_t *codes, const uint8_t *shared, int64_t rows, int64_t cols,
+                             int block, int e, int m, double *y) {
+    if (mxo_check_minifloat(block, e, m, 0) != MXO_OK) return MXO_BAD_ARG;
+    if (rows < 0 || cols < 0 || cols % block != 0) return MXO_BAD_ARG;
+    const int64_t nb = cols / block;
+    const int cmax = (1 << e) - 1;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t cidx = 0; cidx < cols; ++cidx) {
+            const int code = codes[r * cols + cidx];
+            const int sb = shared[r * nb + cidx / block];
+            const int sign = (code >> (e + m)) & 1, c = (code >> m) & cmax, f = code & ((1 << m) - 1);
+            double v = 0.0;
+            if (sb != 0) {
+                const int T = sb - 127;
+                if (c >= 1) v = ldexp(1.0 + ldexp((double)f, -m), c - cmax + T);
+                else v = ldexp(ldexp((double)f, -m), 1 - cmax + T);
+            }
+            y[r * cols + cidx] = sign ? -v : v;
+        }
+    return MXO_OK;
+}
+
 int mxo_set_threads(int n) {
 #ifdef _OPENMP
     if (n > 0) omp_set_num_threads(n);

@@ -55,8 +55,11 @@ def _load():
         lib.mxo_gemm.argtypes = [p, p, i32, p, p, i32, i64, i64, i64, i32, i32, i64, i64, p, p]
         lib.mxo_set_threads.argtypes = [i32]
         lib.mxo_cast.argtypes = [p, p, i64, i64, i32, i32, i32, i32, i32, i32, p, p]
+        lib.mxo_quantize_minifloat.argtypes = [p, i64, i64, i64, i32, i32, i32, i32, p, p]
+        lib.mxo_dequantize_minifloat.argtypes = [p, p, i64, i64, i32, i32, i32, p]
         for f in (lib.mxo_quantize, lib.mxo_quantize_axis0, lib.mxo_dequantize, lib.mxo_pack_bits,
-                  lib.mxo_unpack_bits, lib.mxo_gemm, lib.mxo_set_threads, lib.mxo_cast):
+                  lib.mxo_unpack_bits, lib.mxo_gemm, lib.mxo_set_threads, lib.mxo_cast,
+                  lib.mxo_quantize_minifloat, lib.mxo_dequantize_minifloat):
             f.restype = i32
         _lib = lib
     return _lib
@@ -266,3 +269,30 @@ def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, 
     O[r0:r1] = Osub
     return O, {"S": S, "S_mag": s_mag, "P": P, "pq": pq, "pe": pe, "vq": vq, "ve": ve, "O_mag": o_mag,
                "rows": (r0, r1)}
+
+
+def quantize_minifloat(x: np.ndarray, block: int, e: int, m: int, rounding: int = RNE) -> Tuple[np.ndarray, np.ndarray]:
+    """The paper's other block formats (Section 2): Block Minifloat BMF(block, e, m) -- sign, e exponent bits,
+    m mantissa bits per element, the exponent bias shared by the block -- and, with m = 0, Block Logarithm
+    (powers of two).  Returns codes uint8 [rows, cols] (sign << (e+m) | c << m | f) and the shared byte
+    (top exponent + 127) uint8 [rows, cols/block]; the bit-level reading is stated in the C file."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    assert x.ndim == 2
+    rows, cols = x.shape
+    if block < 1 or cols % block:
+        raise ValueError("cols must be a multiple of block")
+    codes = np.empty((rows, cols), np.uint8)
+    shared = np.empty((rows, cols // block), np.uint8)
+    _check(_load().mxo_quantize_minifloat(_ptr(x), rows, cols, cols, block, e, m, rounding, _ptr(codes), _ptr(shared)),
+           "quantize_minifloat")
+    return codes, shared
+
+
+def dequantize_minifloat(codes: np.ndarray, shared: np.ndarray, block: int, e: int, m: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    shared = np.ascontiguousarray(shared, dtype=np.uint8)
+    rows, cols = codes.shape
+    y = np.empty((rows, cols), np.float64)
+    _check(_load().mxo_dequantize_minifloat(_ptr(codes), _ptr(shared), rows, cols, block, e, m, _ptr(y)),
+           "dequantize_minifloat")
+    return y

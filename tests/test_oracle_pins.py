@@ -624,3 +624,117 @@ def test_attention_steps_against_library_routines():
     assert np.allclose(O, pd @ _vdeq(V, 16, 3), rtol=1e-12, atol=1e-12)
     O2, _ = orc.attention(Q, K, V, 16, 7, 6, 5, 3, scale=D ** -0.5, rows=(8, 16))
     assert np.array_equal(O2[8:16], O[8:16]) and np.all(np.isnan(O2[:8])) and np.all(np.isnan(O2[16:]))
+
+
+# ----------------------------------------------------------------------------------------------
+# Block Minifloat and Block Logarithm (Section 2): the format's value set written out, brute force
+# ----------------------------------------------------------------------------------------------
+def _minifloat_values(T, e, m):
+    """Every non-negative representable value of a block with top exponent T, as exact fractions, indexed
+    by its code integer (c << m | f): the definition, enumerated."""
+    cmax = 2 ** e - 1
+    vals = []
+    for c in range(cmax + 1):
+        for f in range(2 ** m):
+            if c >= 1:
+                vals.append(Fraction(2) ** (c - cmax + T) * (1 + Fraction(f, 2 ** m)))
+            else:
+                vals.append(Fraction(2) ** (1 - cmax + T) * Fraction(f, 2 ** m))
+    return vals
+
+
+def _minifloat_nearest(x, vals, rounding):
+    """Code of the representable value nearest to |x| (ties: even code; RTZ: largest value <= |x|)."""
+    a = abs(Fraction(float(x)))
+    if rounding == orc.RTZ:
+        return max(i for i, v in enumerate(vals) if v <= a)
+    best = min(range(len(vals)), key=lambda i: (abs(vals[i] - a), i & 1))
+    return best
+
+
+@pytest.mark.parametrize("e,m", [(2, 1), (3, 0), (2, 0), (3, 2), (4, 3), (1, 2)])
+def test_minifloat_brute_force(e, m):
+    """Against the enumerated value set: the shared top exponent is the smallest one whose value set reaches
+    the rounded block maximum, and every element takes the nearest value (ties to the even code)."""
+    rng = np.random.default_rng(100 * e + m)
+    block = 8
+    x = (rng.standard_normal((40, 2 * block)) * np.exp2(rng.integers(-6, 6, size=(40, 1)))).astype(np.float32)
+    x[0, :block] = 0.0
+    x[1, 3] = 0.0
+    # exact ties and exact representable values, in a block whose maximum pins T = 0
+    vals0 = _minifloat_values(0, e, m)
+    mids = [float((vals0[i] + vals0[i + 1]) / 2) for i in range(len(vals0) - 1)]
+    x[2, :block] = (mids + [1.0] * block)[:block]
+    x[2, block - 1] = 1.0
+    x[3, :block] = ([float(v) for v in vals0[-block + 1:]] + [1.0] * block)[:block]
+    for rounding in (orc.RNE, orc.RTZ):
+        codes, shared = orc.quantize_minifloat(x, block, e, m, rounding)
+        for r in range(x.shape[0]):
+            for b in range(2):
+                blk = x[r, b * block:(b + 1) * block]
+                amax = np.abs(blk).max()
+                if amax == 0:
+                    assert shared[r, b] == 0 and not codes[r, b * block:(b + 1) * block].any()
+                    continue
+                T = int(shared[r, b]) - 127
+                vals = _minifloat_values(T, e, m)
+                a = Fraction(float(amax))
+                # T is minimal: with T - 1 the maximum would have to saturate (or, for RTZ, lie above the range)
+                if rounding == orc.RNE:
+                    top = vals[-1]
+                    nxt = Fraction(2) ** (T + 1)
+                    assert a < (top + nxt) / 2
+                    lower = _minifloat_values(T - 1, e, m)
+                    assert a >= (lower[-1] + Fraction(2) ** T) / 2
+                else:
+                    assert Fraction(2) ** T <= a < Fraction(2) ** (T + 1)
+                for i, xv in enumerate(blk):
+                    code = int(codes[r, b * block + i])
+                    sign, mag = code >> (e + m), code & (2 ** (e + m) - 1)
+                    assert sign == int(np.signbit(xv))
+                    assert mag == _minifloat_nearest(xv, vals, rounding), (r, b, i, float(xv), T)
+
+
+def test_minifloat_hand_worked_blocks():
+    """BMF(e=2, m=1), block of 4, maximum 3.0: T = 1, cmax = 3, values 0, .25 | .5, .75 | 1, 1.5 | 2, 3.
+    3.0 -> c=3 f=1 (code 7); 1.25 is a tie between 1 (code 4) and 1.5 (code 5) -> 1; -0.6 -> -0.5 (sign, code 2);
+    0.1 -> nearer 0 than 0.25 -> 0.
+    BL(e=2): maximum 3.0 is at the midpoint of 2 and 4 -> T = 2 (values 0, 1, 2, 4), 3.0 is a tie between 2 (code 2)
+    and 4 (code 3) -> 2; 1.5 a tie between 1 (code 1) and 2 (code 2) -> 2; 0.5 a tie between 0 (code 0) and 1 -> 0."""
+    x = np.array([[3.0, 1.25, -0.6, 0.1]], np.float32)
+    codes, shared = orc.quantize_minifloat(x, 4, 2, 1)
+    assert shared.tolist() == [[128]] and codes.tolist() == [[7, 4, 8 + 2, 0]]
+    assert orc.dequantize_minifloat(codes, shared, 4, 2, 1).tolist() == [[3.0, 1.0, -0.5, 0.0]]
+    x = np.array([[3.0, 1.5, -0.5, 0.7]], np.float32)
+    codes, shared = orc.quantize_minifloat(x, 4, 2, 0)
+    assert shared.tolist() == [[129]] and codes.tolist() == [[2, 2, 0 + 4, 1]]
+    assert orc.dequantize_minifloat(codes, shared, 4, 2, 0).tolist() == [[2.0, 2.0, -0.0, 1.0]]
+    codes, shared = orc.quantize_minifloat(x, 4, 2, 0, orc.RTZ)                # toward zero: T = 1, values 0, .5, 1, 2
+    assert shared.tolist() == [[128]] and codes.tolist() == [[3, 2, 4 + 1, 1]]
+
+
+def test_minifloat_invariants():
+    rng = np.random.default_rng(9)
+    for e, m, block in [(4, 3, 16), (3, 4, 32), (7, 0, 16), (5, 2, 8)]:
+        x = (rng.standard_normal((32, 4 * block)) * np.exp2(rng.integers(-20, 20, size=(32, 1)))).astype(np.float32)
+        codes, shared = orc.quantize_minifloat(x, block, e, m)
+        y = orc.dequantize_minifloat(codes, shared, block, e, m)
+        # representable values come back exactly, and quantizing them again changes nothing
+        c2, s2 = orc.quantize_minifloat(y.astype(np.float32), block, e, m)
+        assert np.array_equal(c2, codes) and np.array_equal(s2, shared)
+        # error at most half a step of the value's binade (steps are 2^(k-m), k >= the smallest binade)
+        T = shared.astype(int).repeat(block, axis=1) - 127
+        k = np.maximum(np.floor(np.log2(np.maximum(np.abs(x.astype(np.float64)), 1e-300))), T - (2 ** e - 1) + 1)
+        assert np.all(np.abs(y - x) <= np.exp2(k - m - 1) * (1 + 1e-12))
+        assert np.array_equal(np.signbit(y), np.signbit(x))
+        # scaling by a power of two moves only the shared byte
+        c3, s3 = orc.quantize_minifloat(x * 8.0, block, e, m)
+        assert np.array_equal(c3, codes) and np.array_equal(s3.astype(int), shared.astype(int) + 3)
+        # the block maximum lands in the top binade or one below its top (when T was raised for the carry)
+        cfield = (codes >> m) & (2 ** e - 1)
+        assert np.all(cfield.reshape(32, 4, block).max(axis=2) >= 2 ** e - 2)
+        if m == 0:                                       # block logarithm: powers of two or zero
+            nz = y != 0
+            assert np.all(np.exp2(np.round(np.log2(np.abs(y[nz])))) == np.abs(y[nz]))
+    with pytest.raises(Exception):
+        orc.quantize_minifloat(np.array([[np.inf, 0, 0, 0]], np.float32), 4, 3, 2)
