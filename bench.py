@@ -192,6 +192,19 @@ def main():
                 kernels["quantize_%dx%d_w8_b16x2" % (c.M, c.K)] = {
                     "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
                     "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
+            if c.K == 11008:
+                # the paper's other block formats at the same shape: Block Minifloat (1 + 4 + 3 bits) and Block
+                # Logarithm (1 + 7 bits), one byte per element + one shared byte per block
+                mcodes = torch.empty(c.M * c.K, dtype=torch.uint8, device=dev)
+                mshared = torch.empty(c.M * c.K // c.block, dtype=torch.uint8, device=dev)
+                for name, fm in (("bmf_e4m3", mx.mx_minifloat_format(c.block, 4, 3, mx.MX_RNE)),
+                                 ("bl_e7", mx.mx_minifloat_format(c.block, 7, 0, mx.MX_RNE))):
+                    ms = time_launches(lambda i: mx.mx_quantize_minifloat(qring[i % nring], 1, c.M, c.K, c.K, 0, fm,
+                                                                          mcodes, mshared), 2 * nring)
+                    mbytes = c.M * c.K * (4 + 1 + 1 / c.block)
+                    kernels["quantize_%s_%dx%d_b%d" % (name, c.M, c.K, c.block)] = {
+                        "GBps": round(mbytes / ms / 1e6, 1), "frac_hbm": round(mbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                        "us": round(ms * 1e3, 2), "bytes": int(mbytes)}
             if args.layout == "matrix":
                 ms = time_launches(lambda i: mx.mx_quantize_pack(qring[i % nring], 1, c.M, c.K, c.K, 0, w["fa"], L,
                                                                  w["A"]), 2 * nring)

@@ -136,6 +136,39 @@ MX_API mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t
                         int64_t cols, mx_format f, float* y, void* stream);
 
 /*
+ * The paper's two other block formats (Section 2, "What are MX Formats?"): Block Minifloat, whose
+ * elements are small floating-point numbers sharing the exponent bias of their block, and Block
+ * Logarithm, the same without mantissa bits (every value a power of two or zero).
+ * An element is one byte: sign << (e+m) | c << m | f, with c the exp_bits-wide exponent field and f
+ * the mant_bits-wide mantissa field, 1 + exp_bits + mant_bits <= 8.  With cmax = 2^exp_bits - 1
+ * and the block's shared top exponent T:
+ *     c >= 1:  +-2^(c - cmax + T) * (1 + f / 2^mant_bits)
+ *     c == 0:  +-2^(1 - cmax + T) * (f / 2^mant_bits)         (gradual underflow, and zero)
+ * The shared byte is T + 127 (T in -126..127), 0 for an all-zero block.  T is the exponent of the
+ * block maximum after rounding, elements round to the nearest representable value with ties to the
+ * even code (MX_RNE) or toward zero (MX_RTZ).
+ */
+typedef struct {
+    int32_t block;     /* elements of a row sharing the bias: 8, 16, 32 or 64 */
+    int32_t exp_bits;  /* e, 1..7 */
+    int32_t mant_bits; /* m, 0..6; 0 is the Block Logarithm format */
+    int32_t rounding;  /* MX_RNE or MX_RTZ */
+} mx_minifloat_format;
+
+/*
+ * Quantizer and its inverse for the formats above, blocks along the columns.
+ * x: device fp32, element (b, r, c) at x[b*batch_stride + r*row_stride + c], finite values;
+ *    16-byte aligned with strides that are multiples of 4 elements (else MX_ERR_UNSUPPORTED).
+ * codes: device, batch*rows*cols bytes, 4-byte aligned; shared: batch*rows*(cols/block) bytes.
+ * cols must be a multiple of block.  y: device fp32, dense batch x rows x cols, 16-byte aligned.
+ */
+MX_API mx_status mx_quantize_minifloat(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                                int64_t batch_stride, mx_minifloat_format f, uint8_t* codes, uint8_t* shared,
+                                void* stream);
+MX_API mx_status mx_dequantize_minifloat(const uint8_t* codes, const uint8_t* shared, int64_t batch, int64_t rows,
+                                  int64_t cols, mx_minifloat_format f, float* y, void* stream);
+
+/*
  * Width cast inside the format, without going through floating point (Section 4, the paragraph
  * on mixed-precision quantization: casting mantissas is bit extension or truncation, the
  * exponent takes a shift): canonical form in format fs -> canonical form in format fd, same

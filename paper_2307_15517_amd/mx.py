@@ -22,7 +22,7 @@ MX_LAYOUT_MATRIX = 1
 
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
            "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
-           "mx_gemm_q", "mx_attention", "mx_linear")
+           "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat")
 
 
 class mx_format(ctypes.Structure):
@@ -37,6 +37,12 @@ class mx_format(ctypes.Structure):
 
 def fmt(block: int, mant_bits: int, exp_bits: int = 8, rounding: int = MX_RNE, block_rows: int = 1) -> mx_format:
     return mx_format(block, exp_bits, mant_bits, rounding, block_rows)
+
+
+class mx_minifloat_format(ctypes.Structure):
+    """Mirror of the C struct of the Block Minifloat / Block Logarithm formats: block, exp_bits, mant_bits, rounding."""
+    _fields_ = [("block", ctypes.c_int32), ("exp_bits", ctypes.c_int32), ("mant_bits", ctypes.c_int32),
+                ("rounding", ctypes.c_int32)]
 
 
 class MxError(RuntimeError):
@@ -73,9 +79,11 @@ def load() -> ctypes.CDLL:
     lib.mx_gemm_q.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, vp, mx_format, mx_format, vp, vp]
     lib.mx_attention.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, vp, mx_format, mx_format,
                                  ctypes.c_float, i32, vp, i64, i64, vp]
+    lib.mx_quantize_minifloat.argtypes = [vp, i64, i64, i64, i64, i64, mx_minifloat_format, vp, vp, vp]
+    lib.mx_dequantize_minifloat.argtypes = [vp, vp, i64, i64, i64, mx_minifloat_format, vp, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
     for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
-                 "mx_gemm_q", "mx_attention", "mx_linear"):
+                 "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -193,6 +201,22 @@ def mx_attention(batch, Sq, Sk, D, Q_packed, fq, K_packed, fk, Vt_packed, fv, fp
                             float(scale), layout, _p(O), ldo, o_batch_stride, _stream(stream))
     if check:
         _raise(s, "mx_attention")
+    return s
+
+
+def mx_quantize_minifloat(x, batch, rows, cols, row_stride, batch_stride, f, codes, shared, stream=None,
+                          check: bool = True) -> int:
+    s = load().mx_quantize_minifloat(_p(x), batch, rows, cols, row_stride, batch_stride, f, _p(codes), _p(shared),
+                                     _stream(stream))
+    if check:
+        _raise(s, "mx_quantize_minifloat")
+    return s
+
+
+def mx_dequantize_minifloat(codes, shared, batch, rows, cols, f, y, stream=None, check: bool = True) -> int:
+    s = load().mx_dequantize_minifloat(_p(codes), _p(shared), batch, rows, cols, f, _p(y), _stream(stream))
+    if check:
+        _raise(s, "mx_dequantize_minifloat")
     return s
 
 

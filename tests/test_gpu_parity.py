@@ -1079,3 +1079,71 @@ def test_attention_rejections():
     assert call(fp_=mx.fmt(16, 8, block_rows=2), fv=mx.fmt(16, 8, block_rows=2)) == mx.MX_ERR_UNSUPPORTED
     assert call(Sq=0) == mx.MX_OK
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------------
+# Block Minifloat / Block Logarithm quantizer: bit-exact against the oracle
+# ----------------------------------------------------------------------------------------------
+def run_minifloat(x, block, e, m, rounding=mx.MX_RNE):
+    rows, cols = x.shape[-2:]
+    batch = 1 if x.ndim == 2 else x.shape[0]
+    f = mx.mx_minifloat_format(block, e, m, rounding)
+    xd = dev(x)
+    codes = torch.full((batch * rows * cols,), 0xAA, dtype=torch.uint8, device=DEV)
+    shared = torch.full((batch * rows * (cols // block),), 0xAA, dtype=torch.uint8, device=DEV)
+    mx.mx_quantize_minifloat(xd, batch, rows, cols, cols, rows * cols, f, codes, shared)
+    y = torch.empty((batch, rows, cols), dtype=torch.float32, device=DEV)
+    mx.mx_dequantize_minifloat(codes, shared, batch, rows, cols, f, y)
+    torch.cuda.synchronize()
+    x3 = x.reshape(batch, rows, cols)
+    for b in range(batch):
+        oc, osh = orc.quantize_minifloat(x3[b], block, e, m, rounding)
+        assert np.array_equal(host(shared).reshape(batch, rows, -1)[b], osh), "shared bytes differ"
+        assert np.array_equal(host(codes).reshape(batch, rows, cols)[b], oc), "codes differ"
+        assert np.array_equal(host(y)[b].astype(np.float64), orc.dequantize_minifloat(oc, osh, block, e, m))
+
+
+@pytest.mark.parametrize("block", [8, 16, 32, 64])
+@pytest.mark.parametrize("e,m", [(4, 3), (3, 4), (7, 0), (2, 0), (1, 6), (5, 2)])
+def test_minifloat_quantizer_bit_exact(block, e, m):
+    rng = np.random.default_rng(block * 100 + 10 * e + m)
+    rows, cols = 37, 5 * block                           # ragged against the 256-thread workgroups
+    x = (rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-12, 12, size=(rows, 1)))).astype(np.float32)
+    x[0] = 0.0
+    x[1, ::3] = 0.0
+    x[2] = np.exp2(rng.integers(-8, 8, size=cols)).astype(np.float32)                    # exact powers of two
+    x[3] = (1.5 * np.exp2(rng.integers(-8, 8, size=cols))).astype(np.float32)            # ties of the m = 0 format
+    x[4] = (rng.integers(0, 2 ** (m + 2), size=cols) * 2.0 ** -(m + 1) - 1.0).astype(np.float32)   # half steps: ties
+    x[5] = (rng.standard_normal(cols) * 1e-39).astype(np.float32)                        # fp32 subnormals
+    x[6] = (rng.standard_normal(cols) * 3e38).clip(-3.4e38, 3.4e38).astype(np.float32)   # top of the fp32 range
+    x[7, :block] = 1.0
+    x[7, 0] = np.float32(2.0) - np.float32(2.0 ** -(m + 1))                              # maximum exactly at the carry midpoint
+    for rounding in (mx.MX_RNE, mx.MX_RTZ):
+        run_minifloat(x, block, e, m, rounding)
+
+
+def test_minifloat_workload_shape_and_batch():
+    """The prefill activation shape (2048 x 4096, Student-t with outlier channels) in BMF(32, 4, 3) and
+    BL(32, 7), and a batch of small matrices."""
+    case = inputs.llama7b_prefill()[0]
+    x, _ = inputs.make(case)
+    run_minifloat(x, 32, 4, 3)
+    run_minifloat(x, 32, 7, 0)
+    rng = np.random.default_rng(4)
+    run_minifloat(rng.standard_normal((3, 9, 64)).astype(np.float32), 16, 3, 2)
+
+
+def test_minifloat_rejections():
+    x = torch.zeros((4, 64), dtype=torch.float32, device=DEV)
+    c = torch.zeros(256, dtype=torch.uint8, device=DEV)
+    s = torch.zeros(16, dtype=torch.uint8, device=DEV)
+    q = lambda f, cols=64, xx=x, stride=64: mx.mx_quantize_minifloat(xx, 1, 4, cols, stride, 4 * 64, f, c, s, check=False)
+    F = mx.mx_minifloat_format
+    assert q(F(16, 4, 3, 0)) == mx.MX_OK
+    assert q(F(16, 4, 4, 0)) == mx.MX_ERR_BAD_ARG            # 1 + 4 + 4 bits do not fit a byte
+    assert q(F(16, 0, 3, 0)) == mx.MX_ERR_BAD_ARG
+    assert q(F(12, 4, 3, 0)) == mx.MX_ERR_BAD_ARG
+    assert q(F(16, 4, 3, 2)) == mx.MX_ERR_BAD_ARG
+    assert q(F(16, 4, 3, 0), cols=40) == mx.MX_ERR_BAD_ARG   # not whole blocks
+    assert q(F(16, 4, 3, 0), xx=x.view(-1)[1:], cols=48, stride=48) == mx.MX_ERR_UNSUPPORTED   # rows not 16-byte aligned
+    torch.cuda.synchronize()
