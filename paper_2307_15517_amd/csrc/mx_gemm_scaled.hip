@@ -61,6 +61,20 @@ __device__ __forceinline__ void copy16_to_lds(const uint8_t* uniform_src, uint32
         : "v"(lane_offset), "s"(uniform_src), "s"(lds_addr)
         : "memory", "m0");
 }
+// Three consecutive KiB (one unit) with one setting of m0: the instruction's offset field moves the
+// global address and the LDS address alike.
+__device__ __forceinline__ void copy48_to_lds(const uint8_t* uniform_src, uint32_t lane_offset,
+                                              uint32_t lds_addr) {
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, %1\n\t"
+        "global_load_lds_dwordx4 %0, %1 offset:1024\n\t"
+        "global_load_lds_dwordx4 %0, %1 offset:2048\n\t"
+        :
+        : "v"(lane_offset), "s"(uniform_src), "s"(lds_addr)
+        : "memory", "m0");
+}
 __device__ __forceinline__ void copy4_to_lds(const uint8_t* uniform_src, uint32_t lane_offset,
                                              uint32_t lds_addr) {
     asm volatile(
@@ -93,6 +107,11 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     constexpr int NU = UA + UB;
     constexpr int STAGE = NU * kUnitBytes;
     constexpr int NLOAD = (3 * NU + 3) / 4;            // 1 KiB wave copies per wave per K step
+    // When the units divide among the four waves, a wave copies whole units (three KiB with one
+    // address set-up); otherwise single KiB pieces.
+    constexpr int CP = (NU % 4 == 0) ? 3 : 1;          // KiB per copy item
+    constexpr int NI = NLOAD / CP;                     // copy items per wave per K step
+    static_assert(NI * CP == NLOAD, "items cover the wave's copies");
     constexpr int RA = TM, RB = TN;                    // row tiles per wave: the wave tile is (32*RA) x (32*RB)
     constexpr int NT = 2 * TM + 2 * TN;                // row tiles of the workgroup tile (A then B)
     constexpr int NSC = (NT + 3) / 4;                  // 256-byte scale copies per wave per group of 4 steps
@@ -113,13 +132,13 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     const uint8_t* Bbase = g.B + bz * g.matrixB;
     const int64_t groups = g.ksteps / 4;
 
-    // this wave's share of the global -> LDS copy: copy t moves 1 KiB number (t % 3) of stage unit (t / 3)
-    const uint8_t* src[NLOAD];
-    int dst[NLOAD];
+    // this wave's share of the global -> LDS copy: item t moves KiB (t*CP % 3) .. of stage unit (t*CP / 3)
+    const uint8_t* src[NI];
+    int dst[NI];
 #pragma unroll
-    for (int q = 0; q < NLOAD; ++q) {
-        int t = q * 4 + wave;
-        if (t >= 3 * NU) t = 3 * NU - 1;               // duplicate the last copy instead of branching
+    for (int q = 0; q < NI; ++q) {
+        int t = (q * 4 + wave) * CP;
+        if (t >= 3 * NU) t = 3 * NU - CP;              // duplicate the last item instead of branching
         const int n = t / 3, part = t - 3 * n;
         int64_t u;
         const uint8_t* base;
@@ -169,13 +188,14 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
 
     // Copies are always issued in full, with the K step / group clamped to the last one, so that
     // the number of copies in flight is the same at every step and the vmcnt waits stay exact.
-    auto issue_one = [&](int q, int64_t ks, int stage) {
-        ks = ks < g.ksteps ? ks : g.ksteps - 1;
-        copy16_to_lds(src[q] + ks * kUnitBytes, lane16, lds0 + stage * STAGE + dst[q]);
+    auto copy_item = [&](const uint8_t* from, uint32_t lds_addr) {
+        if constexpr (CP == 3) copy48_to_lds(from, lane16, lds_addr);
+        else copy16_to_lds(from, lane16, lds_addr);
     };
     auto issue = [&](int64_t ks, int stage) {
+        ks = ks < g.ksteps ? ks : g.ksteps - 1;
 #pragma unroll
-        for (int q = 0; q < NLOAD; ++q) issue_one(q, ks, stage);
+        for (int q = 0; q < NI; ++q) copy_item(src[q] + ks * kUnitBytes, lds0 + stage * STAGE + dst[q]);
     };
     auto issue_scale_one = [&](int q, int64_t grp, int slot) {
         grp = grp < groups ? grp : groups - 1;
@@ -190,7 +210,14 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
         const uint4 l0 = *reinterpret_cast<const uint4*>(u + frag_lo(0, lane));
         const uint2 h0 = *reinterpret_cast<const uint2*>(u + frag_hi(0, lane));
         const uint4 l1 = *reinterpret_cast<const uint4*>(u + frag_lo(1, lane));
-        const uint2 h1 = *reinterpret_cast<const uint2*>(u + frag_hi(1, lane));
+        // the two 8-byte parts are 512 bytes apart; read through an address the compiler cannot relate to the
+        // first one, or it fuses them into one two-address read whose four result registers then have to be
+        // copied into the two operand tuples
+        typedef unsigned int u2v __attribute__((ext_vector_type(2)));
+        typedef __attribute__((address_space(3))) const u2v lds_u2v;
+        lds_u2v* u1 = (lds_u2v*)(u + frag_hi(1, lane));
+        asm volatile("" : "+v"(u1));
+        const u2v h1 = *u1;
         f0.d[0] = (int)l0.x; f0.d[1] = (int)l0.y; f0.d[2] = (int)l0.z; f0.d[3] = (int)l0.w;
         f0.d[4] = (int)h0.x; f0.d[5] = (int)h0.y;
         f1.d[0] = (int)l1.x; f1.d[1] = (int)l1.y; f1.d[2] = (int)l1.z; f1.d[3] = (int)l1.w;
@@ -246,6 +273,11 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     }
     constexpr int NM = PA * PB * RA * RB;              // MFMAs per K step
     int cur = 0;                                       // stage of the current step: ks % S
+    // byte offset, inside a unit row, of the K step whose copies the current step issues (step ks + S,
+    // clamped to the last one): carried from step to step instead of being derived from ks each time
+    const uint32_t last_off = (uint32_t)((g.ksteps - 1) * kUnitBytes);
+    uint32_t copy_off = (uint32_t)S * kUnitBytes;
+    copy_off = copy_off < last_off ? copy_off : last_off;
     for (int64_t ks4 = 0; ks4 < groups; ++ks4) {
 #pragma unroll
         for (int t = 0; t < RA; ++t) scA[t] = nxA[t];
@@ -259,12 +291,12 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
             const int nxt = cur + 1 == S ? 0 : cur + 1;
             // side work of this step, in issue order: LDS reads for step ks+1, copies for step ks+S,
             // at j == 0 the scale copies of the next group, at j == 3 the read of those scales
-            constexpr int NAUX = (NUA + NUB) + NLOAD + (j == 0 ? NSC : 0) + (j == 3 ? 1 : 0);
+            constexpr int NAUX = (NUA + NUB) + NI + (j == 0 ? NSC : 0) + (j == 3 ? 1 : 0);
             auto aux = [&](int x) {
                 if (x < NUA + NUB) { read_unit(x, nxt, std::integral_constant<int, set ^ 1>{}); return; }
                 x -= NUA + NUB;
-                if (x < NLOAD) { issue_one(x, ks + S, cur); return; }
-                x -= NLOAD;
+                if (x < NI) { copy_item(src[x] + copy_off, lds0 + cur * STAGE + dst[x]); return; }
+                x -= NI;
                 if (j == 0) issue_scale_one(x, ks4 + 1, (int)((ks4 + 1) & 1));
                 if (j == 3) read_scales((int)((ks4 + 1) & 1), nxA, nxB);
             };
@@ -288,6 +320,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
                 __builtin_amdgcn_sched_barrier(0);        // pin the interleaving as written
             }
             cur = nxt;
+            copy_off = copy_off + kUnitBytes < last_off ? copy_off + kUnitBytes : last_off;
         };
         kstep(std::integral_constant<int, 0>{});
         kstep(std::integral_constant<int, 1>{});
@@ -441,6 +474,7 @@ mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
     }
     const int64_t tiles_m = ceil_div(g.M, 64 * TM), tiles_n = ceil_div(g.N, 64 * TN);
     if (tiles_m * tiles_n > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+    if (g.ksteps * kUnitBytes > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;       // 32-bit offsets along K
     g.tiles_m = (int32_t)tiles_m;
     g.tiles_n = (int32_t)tiles_n;
     dim3 grid((unsigned)(ceil_div(tiles_m * tiles_n, 8) * 8), (unsigned)batch);
