@@ -315,6 +315,9 @@ def main():
         ms = time_launches(lambda i: mx.mx_quantize(Vd, heads, seq, dim, dim, seq * dim, 0, fv, vmant, vexps), 20)
         attn_entry("quantize_v_along_seq", ms, n_el * (4 + dens(fv)))
         mx.mx_pack(vmant, vexps, heads, dim, seq, fv, LA, Bv)
+        if LA == mx.MX_LAYOUT_MATRIX:
+            ms = time_launches(lambda i: mx.mx_quantize_pack_axis0(Vd, heads, seq, dim, dim, seq * dim, fv, LA, Bv), 20)
+            attn_entry("quantize_pack_v_along_seq", ms, n_el * 4 + Bv.numel())
         ms = time_launches(lambda i: mx.mx_gemm(heads, seq, dim, seq, Ap, fpp, Bv, fv, LA, Od, dim, seq * dim), 10)
         attn_entry("output_gemm", ms, Ap.numel() + Bv.numel() + 4 * n_el, 2.0 * heads * seq * seq * dim)
         del Ss, Ps, Ap

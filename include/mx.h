@@ -205,6 +205,19 @@ MX_API mx_status mx_quantize_pack(const float* x, int64_t batch, int64_t rows, i
                                   int64_t row_stride, int64_t batch_stride, mx_format f, int32_t layout,
                                   void* packed, void* stream);
 
+/*
+ * mx_quantize along axis 0 and mx_pack in one pass: x [rows x cols] is quantized with blocks of
+ * f.block consecutive elements DOWN each column (the strided axis) and written as the packed operand
+ * of the transposed matrix, cols x rows -- exactly the bytes mx_pack gives from the canonical form
+ * that mx_quantize (axis 0) produces.  This is how the V operand of P V is prepared (V [keys x d] is
+ * reduced over the keys: Fig. 1, and mx_attention's Vt_packed).  rows must be a multiple of f.block.
+ * Same pointer rules as mx_quantize_pack; `packed` holds mx_packed_bytes(batch, cols, rows, f, layout)
+ * bytes.  Built for MX_LAYOUT_MATRIX with blocks of 16 (block_rows 1); else MX_ERR_UNSUPPORTED.
+ */
+MX_API mx_status mx_quantize_pack_axis0(const float* x, int64_t batch, int64_t rows, int64_t cols,
+                                        int64_t row_stride, int64_t batch_stride, mx_format f, int32_t layout,
+                                        void* packed, void* stream);
+
 /* Exact inverse of mx_pack. */
 MX_API mx_status mx_unpack(const void* packed, int64_t batch, int64_t rows, int64_t cols, mx_format f,
                     int32_t layout, uint8_t* mant, uint8_t* exps, void* stream);

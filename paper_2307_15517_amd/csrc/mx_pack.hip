@@ -172,3 +172,24 @@ extern "C" mx_status mx_quantize_pack(const float* x, int64_t batch, int64_t row
     return quantize_pack_fragment(x, batch, rows, cols, row_stride, batch_stride, f, (uint8_t*)packed,
                                   (hipStream_t)stream);
 }
+
+namespace mx {
+mx_status quantize_pack_bf16_axis0(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                                   int64_t batch_stride, mx_format f, uint8_t* packed, hipStream_t st);
+}
+
+extern "C" mx_status mx_quantize_pack_axis0(const float* x, int64_t batch, int64_t rows, int64_t cols,
+                                            int64_t row_stride, int64_t batch_stride, mx_format f, int32_t layout,
+                                            void* packed, void* stream) {
+    // the operand that comes out is x^T: cols x rows, blocks along its columns (the rows of x)
+    mx_status s = check_pack_args(batch, cols, rows, f, layout);
+    if (s != MX_OK) return s;
+    if (row_stride < cols) return MX_ERR_BAD_ARG;
+    if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
+    if (layout != MX_LAYOUT_MATRIX || f.block != 16 || f.block_rows != 1) return MX_ERR_UNSUPPORTED;
+    if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
+    if (!x || !packed || ((uintptr_t)x & 3) || ((uintptr_t)packed & 255)) return MX_ERR_BAD_ARG;
+    if (batch > 65535) return MX_ERR_UNSUPPORTED;
+    return quantize_pack_bf16_axis0(x, batch, rows, cols, row_stride, batch_stride, f, (uint8_t*)packed,
+                                    (hipStream_t)stream);
+}

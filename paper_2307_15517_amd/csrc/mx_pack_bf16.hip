@@ -175,6 +175,111 @@ mx_status launch_bf_qpack(const BfQPackArgs& a, int64_t batch, int rnd, hipStrea
     return MX_OK;
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// fp32 -> layout with the blocks running DOWN the columns of x (the strided axis), i.e. the packed
+// operand of x^T [cols x rows]: what mx_quantize with axis 0 followed by mx_pack gives.  This is the
+// V operand of attention: V [keys x d] is reduced over the keys in P V, so its blocks run along the
+// keys and the operand is V^T [d x keys].
+// One workgroup of four waves per 64 rows (four blocks) x 128 columns of x: the tile is read as whole
+// row segments of 512 bytes (two rows per wave instruction) into LDS; wave j then owns output row tile
+// j of the workgroup (32 columns of x), lane 32*h + i reads half h of each block of column i down the
+// LDS tile (32 consecutive floats per half wave: conflict-free with the pitch below), completes the
+// block maximum with the partner lane, quantizes and stores 16 bytes per fragment.
+// ------------------------------------------------------------------------------------------------
+struct BfQPackTArgs {
+    const float* x;
+    uint8_t* packed;
+    int64_t rows, cols, row_stride, batch_stride;     // of x
+    BfGeom g;                                          // of the operand: cols x rows
+    int32_t bias, emax;
+    int32_t vec;                                       // 16-byte loads are aligned
+};
+
+constexpr int kBfTPitch = 128 + 4;     // floats per LDS tile row: the two lane halves (8 rows apart) land 32 banks apart
+
+template <int W, int RND>
+__global__ __launch_bounds__(256) void quantize_pack_bf16_axis0_kernel(BfQPackTArgs a) {
+    __shared__ __attribute__((aligned(16))) float tile[64 * kBfTPitch];
+    constexpr float qmax = (float)((1 << (W - 1)) - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int i = lane & 31, h = lane >> 5;
+    const int64_t r0 = (int64_t)blockIdx.x * 64;       // first row of x (first key) of the tile
+    const int64_t c0 = (int64_t)blockIdx.y * 128;      // first column of x
+    const int64_t b = blockIdx.z;
+    const float* xb = a.x + b * a.batch_stride;
+
+    // 64 rows x 128 columns: a thread loads four columns of a row; 32 threads cover a row, a workgroup 8 rows
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const int rr = p * 8 + (threadIdx.x >> 5);
+        const int64_t row = r0 + rr, col = c0 + (threadIdx.x & 31) * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < a.rows) {
+            const float* src = xb + row * a.row_stride + col;
+            if (a.vec && col + 3 < a.cols) {
+                v = *reinterpret_cast<const float4*>(src);
+            } else {
+                if (col < a.cols) v.x = src[0];
+                if (col + 1 < a.cols) v.y = src[1];
+                if (col + 2 < a.cols) v.z = src[2];
+                if (col + 3 < a.cols) v.w = src[3];
+            }
+        }
+        *reinterpret_cast<float4*>(tile + rr * kBfTPitch + (threadIdx.x & 31) * 4) = v;
+    }
+    __syncthreads();
+
+    const int64_t rt = blockIdx.y * 4 + wave;          // output row tile: columns c0 + 32*wave .. of x
+    if (rt >= a.g.row_tiles) return;
+    uint8_t* base = a.packed + b * a.g.matrix;
+    const int64_t orow = rt * 32 + i;                  // output row = column of x
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {                      // block f of the tile: rows 16*f .. 16*f+15 of x
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = tile[(16 * f + 8 * h + e) * kBfTPitch + 32 * wave + i];
+        uint32_t am = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t ab = __float_as_uint(v[e]) & 0x7fffffffu;
+            am = ab > am ? ab : am;
+        }
+        const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
+        am = o > am ? o : am;
+        const int ef = (int)(am >> 23);
+        int E = ef == 0 ? -127 : ef - 127;
+        E = E < -a.bias ? -a.bias : E;
+        E = E > a.emax ? a.emax : E;
+        uint32_t out[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float sc = __builtin_ldexpf(v[e], (W - 2) - E);
+            float r = RND == MX_RNE ? __builtin_rintf(sc) : __builtin_truncf(sc);
+            r = __builtin_fminf(__builtin_fmaxf(r, -qmax), qmax);
+            r += 0.0f;                                   // -0.0 (a small negative rounded to zero) -> +0.0
+            out[e >> 1] |= bf16_of(r, E - (W - 2)) << (16 * (e & 1));
+        }
+        const int64_t kf = blockIdx.x * 4 + f;           // block along the operand's K (the rows of x)
+        if (kf < a.g.ksteps * 2)
+            *reinterpret_cast<uint4*>(base + bf_frag(a.g, rt, kf >> 1, (int)(kf & 1), lane)) =
+                make_uint4(out[0], out[1], out[2], out[3]);
+        if (h == 0 && orow < a.cols && kf < a.g.nblk) base[a.g.frag_bytes + orow * a.g.nblk + kf] = (uint8_t)(E + a.bias);
+    }
+}
+
+template <int W>
+mx_status launch_bf_qpack_t(const BfQPackTArgs& a, int64_t batch, int rnd, hipStream_t st) {
+    // the K steps of the operand are padded to a multiple of 2 (64 rows of x): the grid covers the padding too
+    dim3 grid((unsigned)(a.g.ksteps / 2), (unsigned)ceil_div(a.g.row_tiles, 4), (unsigned)batch);
+    if (rnd == MX_RNE)
+        hipLaunchKernelGGL((quantize_pack_bf16_axis0_kernel<W, MX_RNE>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((quantize_pack_bf16_axis0_kernel<W, MX_RTZ>), grid, dim3(256), 0, st, a);
+    MX_HIP_LAUNCH_CHECK();
+    return MX_OK;
+}
+
 }  // namespace
 
 mx_status pack_bf16(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows, int64_t cols,
@@ -216,4 +321,28 @@ mx_status quantize_pack_bf16(const float* x, int64_t batch, int64_t rows, int64_
     return MX_ERR_BAD_ARG;
 }
 
+// x [rows x cols] with blocks down the columns -> packed operand of x^T [cols x rows].
+mx_status quantize_pack_bf16_axis0(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                                   int64_t batch_stride, mx_format f, uint8_t* packed, hipStream_t st) {
+    BfQPackTArgs a;
+    a.x = x; a.packed = packed; a.rows = rows; a.cols = cols;
+    a.row_stride = row_stride; a.batch_stride = batch_stride;
+    a.g = bf_geom(cols, rows);
+    a.bias = (1 << (f.exp_bits - 1)) - 1;
+    a.emax = ((1 << f.exp_bits) - 1) - a.bias;
+    a.vec = (((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0 && (batch_stride & 3) == 0) ? 1 : 0;
+    if (a.g.ksteps / 2 > 0x7fffffffLL || ceil_div(a.g.row_tiles, 4) > 65535) return MX_ERR_UNSUPPORTED;
+    switch (f.mant_bits) {
+        case 2: return launch_bf_qpack_t<2>(a, batch, f.rounding, st);
+        case 3: return launch_bf_qpack_t<3>(a, batch, f.rounding, st);
+        case 4: return launch_bf_qpack_t<4>(a, batch, f.rounding, st);
+        case 5: return launch_bf_qpack_t<5>(a, batch, f.rounding, st);
+        case 6: return launch_bf_qpack_t<6>(a, batch, f.rounding, st);
+        case 7: return launch_bf_qpack_t<7>(a, batch, f.rounding, st);
+        case 8: return launch_bf_qpack_t<8>(a, batch, f.rounding, st);
+    }
+    return MX_ERR_BAD_ARG;
+}
+
 }  // namespace mx
+

@@ -21,7 +21,8 @@ MX_LAYOUT_FRAGMENT = 0
 MX_LAYOUT_MATRIX = 1
 
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
-           "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
+           "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0", "mx_unpack",
+           "mx_gemm",
            "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat")
 
 
@@ -74,6 +75,7 @@ def load() -> ctypes.CDLL:
     lib.mx_packed_bytes.argtypes, lib.mx_packed_bytes.restype = [i64, i64, i64, mx_format, i32], sz
     lib.mx_pack.argtypes = [vp, vp, i64, i64, i64, mx_format, i32, vp, vp]
     lib.mx_quantize_pack.argtypes = [vp, i64, i64, i64, i64, i64, mx_format, i32, vp, vp]
+    lib.mx_quantize_pack_axis0.argtypes = [vp, i64, i64, i64, i64, i64, mx_format, i32, vp, vp]
     lib.mx_unpack.argtypes = [vp, i64, i64, i64, mx_format, i32, vp, vp, vp]
     lib.mx_gemm.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, i64, i64, vp]
     lib.mx_gemm_q.argtypes = [i64, i64, i64, i64, vp, mx_format, vp, mx_format, i32, vp, vp, mx_format, mx_format, vp, vp]
@@ -82,7 +84,8 @@ def load() -> ctypes.CDLL:
     lib.mx_quantize_minifloat.argtypes = [vp, i64, i64, i64, i64, i64, mx_minifloat_format, vp, vp, vp]
     lib.mx_dequantize_minifloat.argtypes = [vp, vp, i64, i64, i64, mx_minifloat_format, vp, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
-    for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_unpack", "mx_gemm",
+    for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0",
+                 "mx_unpack", "mx_gemm",
                  "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat"):
         getattr(lib, name).restype = i32
     _lib = lib
@@ -167,6 +170,15 @@ def mx_quantize_pack(x, batch, rows, cols, row_stride, batch_stride, f, layout, 
                                 _stream(stream))
     if check:
         _raise(s, "mx_quantize_pack")
+    return s
+
+
+def mx_quantize_pack_axis0(x, batch, rows, cols, row_stride, batch_stride, f, layout, packed, stream=None,
+                           check: bool = True) -> int:
+    s = load().mx_quantize_pack_axis0(_p(x), batch, rows, cols, row_stride, batch_stride, f, layout, _p(packed),
+                                      _stream(stream))
+    if check:
+        _raise(s, "mx_quantize_pack_axis0")
     return s
 
 

@@ -1147,3 +1147,56 @@ def test_minifloat_rejections():
     assert q(F(16, 4, 3, 0), cols=40) == mx.MX_ERR_BAD_ARG   # not whole blocks
     assert q(F(16, 4, 3, 0), xx=x.view(-1)[1:], cols=48, stride=48) == mx.MX_ERR_UNSUPPORTED   # rows not 16-byte aligned
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------------
+# mx_quantize_pack_axis0: blocks down the columns, packed as the transposed operand
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,cols,w,rounding,e", [(64, 128, 8, mx.MX_RNE, 8), (272, 96, 3, mx.MX_RNE, 8),
+                                                    (16, 16, 5, mx.MX_RTZ, 8), (2080, 130, 6, mx.MX_RNE, 5),
+                                                    (48, 33, 2, mx.MX_RTZ, 4)])
+def test_quantize_pack_axis0_equals_quantize_then_pack(rows, cols, w, rounding, e):
+    """Same bytes as mx_quantize (axis 0) followed by mx_pack -- padding included -- and the canonical form
+    recovered by mx_unpack is the oracle's; ragged tiles, unaligned row pitch, narrow exponents, a batch."""
+    rng = np.random.default_rng(rows + cols)
+    batch = 3
+    x = (rng.standard_normal((batch, rows, cols + 3)) * np.exp2(rng.integers(-10, 10, size=(batch, 1, cols + 3)))).astype(np.float32)
+    x[0, :16, 0] = 0.0
+    f = mx.fmt(16, w, e, rounding)
+    xd = dev(x)
+    xv = xd[:, :, :cols]
+    vm, ve = mx.quantize(xv, f, axis=0)
+    want = mx.pack(vm, ve, batch, cols, rows, f, MAT)
+    got = torch.full((mx.mx_packed_bytes(batch, cols, rows, f, MAT),), 0x5A, dtype=torch.uint8, device=DEV)
+    mx.mx_quantize_pack_axis0(xv, batch, rows, cols, cols + 3, rows * (cols + 3), f, MAT, got)
+    torch.cuda.synchronize()
+    # a packed matrix is its fragments, its exponent bytes, and alignment padding up to 256 bytes that no one writes
+    valid = ((cols + 31) // 32) * (((rows + 31) // 32 + 1) // 2 * 2) * 2048 + cols * (rows // 16)
+    per = mx.mx_packed_bytes(1, cols, rows, f, MAT)
+    assert per == (valid + 255) // 256 * 256
+    assert torch.equal(got.view(batch, per)[:, :valid], want.view(batch, per)[:, :valid])
+    assert bool((got.view(batch, per)[:, valid:] == 0x5A).all())
+    um, ue = mx.unpack(got, batch, cols, rows, f, MAT)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        oq, oe = orc.quantize(x[b, :, :cols], 16, w, e, rounding, axis=0)
+        assert np.array_equal(host(um).reshape(batch, -1)[b], orc.pack_bits(oq, w).reshape(-1))
+        assert np.array_equal(host(ue).reshape(batch, -1)[b], oe.reshape(-1))
+
+
+def test_quantize_pack_axis0_workload_and_rejections():
+    heads, seq, dim = 32, 2048, 128
+    _, _, V = inputs.attention_qkv(0, heads, seq, dim)
+    f = mx.fmt(16, 3)
+    Vd = dev(V)
+    vm, ve = mx.quantize(Vd, f, axis=0)
+    want = mx.pack(vm, ve, heads, dim, seq, f, MAT)
+    got = torch.empty_like(want)
+    mx.mx_quantize_pack_axis0(Vd, heads, seq, dim, dim, seq * dim, f, MAT, got)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)             # 128 * 128 exponent bytes: no alignment padding at this shape
+    call = lambda ff, layout=MAT, rows=seq: mx.mx_quantize_pack_axis0(Vd, heads, rows, dim, dim, seq * dim, ff, layout, got, check=False)
+    assert call(mx.fmt(32, 4)) == mx.MX_ERR_UNSUPPORTED
+    assert call(f, mx.MX_LAYOUT_FRAGMENT) == mx.MX_ERR_UNSUPPORTED
+    assert call(f, rows=seq - 8) == mx.MX_ERR_BAD_ARG       # not whole blocks down the columns
+    torch.cuda.synchronize()
