@@ -1200,3 +1200,57 @@ def test_quantize_pack_axis0_workload_and_rejections():
     assert call(f, mx.MX_LAYOUT_FRAGMENT) == mx.MX_ERR_UNSUPPORTED
     assert call(f, rows=seq - 8) == mx.MX_ERR_BAD_ARG       # not whole blocks down the columns
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------------
+# The entry points allocate nothing and touch only the caller's stream: a graph can capture them
+# ----------------------------------------------------------------------------------------------
+def test_calls_captured_in_a_graph_replay_the_same_bits():
+    """A decode step (three mx_linear calls), a prefill product and an attention call captured into one
+    graph; every replay, with eager work and synchronisation in between, gives the eager bits."""
+    cases = inputs.llama13b_decode(1)[:2]
+    work = []
+    for c in cases:
+        x, wt = inputs.make(c)
+        fa, fb = mx.fmt(c.block, c.wx), mx.fmt(c.block, c.ww)
+        bm, be = mx.quantize(dev(wt), fb)
+        work.append((dev(x), c, fa, torch.zeros(mx.mx_packed_bytes(1, 1, c.K, fa), dtype=torch.uint8, device=DEV),
+                     mx.pack(bm, be, 1, c.N, c.K, fb), fb, torch.zeros((1, c.N), dtype=torch.float32, device=DEV)))
+    rng = np.random.default_rng(12)
+    f8, f4, f16 = mx.fmt(32, 8), mx.fmt(32, 4), mx.fmt(16, 6)
+    X = dev(rng.standard_normal((256, 512)).astype(np.float32))
+    W = mx.quantize_pack(dev((rng.standard_normal((384, 512)) * 0.05).astype(np.float32)), f4, MAT)
+    A = torch.zeros(mx.mx_packed_bytes(1, 256, 512, f8, MAT), dtype=torch.uint8, device=DEV)
+    Y = torch.zeros((256, 384), dtype=torch.float32, device=DEV)
+    Q, K, V = (dev(rng.standard_normal((2, 96, 64)).astype(np.float32)) for _ in range(3))
+    Qp, Kp = (torch.zeros(mx.mx_packed_bytes(2, 96, 64, f16, MAT), dtype=torch.uint8, device=DEV) for _ in range(2))
+    Vp = torch.zeros(mx.mx_packed_bytes(2, 64, 96, f16, MAT), dtype=torch.uint8, device=DEV)
+    O = torch.zeros((2, 96, 64), dtype=torch.float32, device=DEV)
+
+    def step():
+        for xd, c, fa, scratch, B, fb, y in work:
+            mx.mx_linear(xd, 1, c.K, c.K, fa, scratch, B, c.N, fb, mx.MX_LAYOUT_FRAGMENT, y, c.N)
+        mx.mx_quantize_pack(X, 1, 256, 512, 512, 0, f8, MAT, A)
+        mx.mx_gemm(1, 256, 384, 512, A, f8, W, f4, MAT, Y, 384, 256 * 384)
+        mx.mx_quantize_pack(Q, 2, 96, 64, 64, 96 * 64, f16, MAT, Qp)
+        mx.mx_quantize_pack(K, 2, 96, 64, 64, 96 * 64, f16, MAT, Kp)
+        mx.mx_quantize_pack_axis0(V, 2, 96, 64, 64, 96 * 64, f16, MAT, Vp)
+        mx.mx_attention(2, 96, 96, 64, Qp, f16, Kp, f16, Vp, f16, f16, 0.125, MAT, O, 64, 96 * 64)
+
+    outs = [w[-1] for w in work] + [Y, O]
+    step()
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float(rep + 1))                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, w in zip(outs, want):
+            assert torch.equal(o, w), "replay %d differs" % rep
