@@ -87,31 +87,60 @@ __global__ __launch_bounds__(256) void quantize_minifloat_kernel(MiniArgs a) {
                 T = T < -126 ? -126 : T;
                 T = T > 127 ? 127 : T;
                 const int L = T - cmax + 1;
+                // Rounding happens in the fp32 bit pattern.  At or above the format's smallest normal value
+                // 2^L the result keeps m fraction bits: add half of the dropped field (less one, plus the
+                // parity bit that sends a tie to the even code) and clear the field -- a carry runs into the
+                // exponent by itself -- and the code integer c << m | f is the kept bits minus a constant.
+                // Below 2^L the step is fixed at 2^(L-m): adding 2^(L-m+23) makes the fp32 adder round to
+                // that step (ties to even), and the code integer is the low bits of the sum.
+                const int sb = 23 - m;                                          // dropped fraction bits
+                const uint32_t keep = ~((1u << sb) - 1u), half_m1 = (1u << (sb - 1)) - 1u;
+                const uint32_t code_max = (1u << (e + m)) - 1u;
+                const uint32_t rebase = (uint32_t)(126 + L) << m;               // may wrap: used modulo 2^32
+                const bool low_ok = L >= -126;                                  // 2^L is an fp32 normal
+                const uint32_t minnorm = low_ok ? (uint32_t)(L + 127) << 23 : 0x00800000u;
+                const bool magic_overflows = L - m + 23 > 127;
+                const float magic = __uint_as_float((uint32_t)((low_ok && !magic_overflows ? L : -126) - m + 23 + 127) << 23);
+                const uint32_t par0 = m == 0 ? (uint32_t)(L & 1) : 0u;         // m = 0: the code's parity is the exponent's
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t bits = __float_as_uint(xv[i]);
                     const uint32_t ab = bits & 0x7fffffffu;
                     const uint32_t sign = bits >> 31;
-                    // |x| = sig * 2^(ex - 23), sig a 24-bit integer with its top bit set (or x = 0)
-                    uint32_t sig;
-                    int ex;
-                    significand(ab, sig, ex);
-                    int k = ex < L ? L : ex;                                      // binade of the result
-                    int sh = 23 - m + (k - ex);                                   // |x| / 2^(k - m) = sig / 2^sh
-                    sh = sh > 31 ? 31 : sh;                                       // sig < 2^24: the quotient is 0 either way
-                    uint32_t n = sig >> sh;
-                    const uint32_t rem = sig & ((1u << sh) - 1u), half = 1u << (sh - 1);
-                    if (a.rnd == MX_RNE) {
-                        // code integer of the lower neighbour: its parity decides a tie
-                        const uint32_t c_lo = n >= (1u << m) ? (uint32_t)(k - L + 1) : 0u;
-                        const uint32_t odd = m == 0 ? (c_lo & 1u) : (n & 1u);
-                        n += (rem > half || (rem == half && odd)) ? 1u : 0u;
+                    uint32_t code;
+                    if (ab != 0 && ab < minnorm && (!low_ok || magic_overflows)) {
+                        // rare: an fp32 subnormal that the format still resolves (very wide exponent fields), or an
+                        // underflow step too large for the addition trick (blocks near the top of the fp32 range): integers
+                        uint32_t sig;
+                        int ex;
+                        significand(ab, sig, ex);
+                        int k = ex < L ? L : ex;
+                        int sh = 23 - m + (k - ex);
+                        sh = sh > 31 ? 31 : sh;
+                        uint32_t n = sig >> sh;
+                        const uint32_t rem = sig & ((1u << sh) - 1u), half = 1u << (sh - 1);
+                        if (a.rnd == MX_RNE) {
+                            const uint32_t c_lo = n >= (1u << m) ? (uint32_t)(k - L + 1) : 0u;
+                            const uint32_t odd = m == 0 ? (c_lo & 1u) : (n & 1u);
+                            n += (rem > half || (rem == half && odd)) ? 1u : 0u;
+                        }
+                        if (n == (2u << m)) { k += 1; n = 1u << m; }
+                        const uint32_t cf = n >= (1u << m) ? (uint32_t)(k - L + 1) : 0u;
+                        code = (cf << m) | (n & ((1u << m) - 1u));
+                    } else {
+                        // normal range of the format
+                        uint32_t r = ab;
+                        if (a.rnd == MX_RNE) r += half_m1 + (((ab >> sb) & 1u) ^ par0);
+                        uint32_t code_n = ((r & keep) >> sb) - rebase;
+                        // underflow range of the format
+                        uint32_t code_s;
+                        if (a.rnd == MX_RNE) code_s = __float_as_uint(__uint_as_float(ab) + magic) & 0x7fffffu;
+                        else code_s = (uint32_t)__builtin_ldexpf(__uint_as_float(ab), m - L);   // conversion truncates
+                        code = ab < minnorm ? (low_ok ? code_s : 0u) : code_n;
+                        code = ab == 0 ? 0u : code;
                     }
-                    if (n == (2u << m)) { k += 1; n = 1u << m; }                  // carry into the next binade
-                    if (k > T) { k = T; n = (2u << m) - 1u; }                      // saturate (clamped T only)
-                    const uint32_t cf = n >= (1u << m) ? (uint32_t)(k - L + 1) : 0u;
-                    const uint32_t ff = n & ((1u << m) - 1u);
-                    out |= ((sign << (e + m)) | (cf << m) | ff) << (8 * i);
+                    code = code > code_max ? code_max : code;                   // saturate (clamped T only)
+                    out |= ((sign << (e + m)) | code) << (8 * i);
                 }
                 sbyte = (uint8_t)(T + 127);
             }
