@@ -330,6 +330,15 @@ def main():
             attn_entry("fused_scores_softmax_quantize_output", ms, Aq.numel() + Bk.numel() + Bv.numel() + 4 * n_el,
                        4.0 * heads * seq * seq * dim)
 
+            def whole(i):                               # from fp32 Q, K, V to fp32 O: four launches
+                mx.mx_quantize_pack(Qd, heads, seq, dim, dim, seq * dim, fq, LA, Aq)
+                mx.mx_quantize_pack(Kd, heads, seq, dim, dim, seq * dim, fk, LA, Bk)
+                mx.mx_quantize_pack_axis0(Vd, heads, seq, dim, dim, seq * dim, fv, LA, Bv)
+                mx.mx_attention(heads, seq, seq, dim, Aq, fq, Bk, fk, Bv, fv, fpp, dim ** -0.5, LA, Ods[i % 2], dim,
+                                seq * dim)
+            ms = time_launches(whole, 10)
+            attn_entry("from_fp32_qkv_to_output", ms, 4 * 4 * n_el, 4.0 * heads * seq * seq * dim)
+
     # ---------------------------------------------------------------- the oracle on the host cores
     cpu = None
     if not args.no_cpu_baseline:
