@@ -247,35 +247,74 @@ struct QuantAxis0Args {
 };
 
 // Blocks down the rows of each column; the output is the canonical form of the transposed
-// matrix.  One lane owns one block (B strided loads, coalesced across the lanes' columns).
+// matrix.  A workgroup takes 256 rows x 32 columns: the tile is read as row segments of 128 bytes
+// and written into LDS transposed, so that a thread then finds 8 consecutive rows of one column as
+// two 16-byte reads; consecutive lanes take consecutive octets of a column, i.e. the B/8 lanes of a
+// block are neighbours (DPP maximum) and a half wave stores 32*W contiguous bytes of one output row.
+constexpr int kAxis0Rows = 256, kAxis0Cols = 32, kAxis0Pitch = kAxis0Rows + 4;
+
 template <int W, int B, int RND>
 __global__ __launch_bounds__(256) void quantize_axis0_kernel(QuantAxis0Args a) {
-    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t rb = blockIdx.y;            // block index along the rows
+    constexpr int LPB = B / 8;
+    __shared__ __attribute__((aligned(16))) float tile[kAxis0Cols * kAxis0Pitch];
+    const int64_t r0 = (int64_t)blockIdx.x * kAxis0Rows, c0 = (int64_t)blockIdx.y * kAxis0Cols;
     const int64_t b = blockIdx.z;
-    if (c >= a.cols) return;
-    const float* src = a.x + b * a.batch_stride + rb * B * a.row_stride + c;
-    float v[B];
+    const float* xb = a.x + b * a.batch_stride;
+    const bool vec = (((uintptr_t)a.x & 15) == 0) && (a.row_stride & 3) == 0 && (a.batch_stride & 3) == 0;
+    const int tc = (threadIdx.x & 7) * 4, tr = threadIdx.x >> 3;       // 8 threads cover a row segment, 32 rows per pass
+    float4 v[kAxis0Rows / 32];
 #pragma unroll
-    for (int i = 0; i < B; ++i) v[i] = src[i * a.row_stride];
-    uint32_t am = 0;
-#pragma unroll
-    for (int i = 0; i < B; ++i) {
-        uint32_t ab = __float_as_uint(v[i]) & 0x7fffffffu;
-        am = ab > am ? ab : am;
+    for (int p = 0; p < kAxis0Rows / 32; ++p) {
+        const int64_t row = r0 + p * 32 + tr, col = c0 + tc;
+        v[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < a.rows) {
+            const float* src = xb + row * a.row_stride + col;
+            if (vec && col + 3 < a.cols) {
+                v[p] = *reinterpret_cast<const float4*>(src);
+            } else {
+                if (col < a.cols) v[p].x = src[0];
+                if (col + 1 < a.cols) v[p].y = src[1];
+                if (col + 2 < a.cols) v[p].z = src[2];
+                if (col + 3 < a.cols) v[p].w = src[3];
+            }
+        }
     }
-    const int E = block_exponent(am, a.bias, a.emax);
-    const int shift = (W - 2) - E;
-    const int64_t nb = a.rows / B;
-    uint8_t* mrow = a.mant + (b * a.cols + c) * (a.rows * W / 8) + rb * (B * W / 8);
 #pragma unroll
-    for (int o = 0; o < B / 8; ++o) {
+    for (int p = 0; p < kAxis0Rows / 32; ++p) {
+        float* dst = tile + tc * kAxis0Pitch + p * 32 + tr;
+        dst[0] = v[p].x;
+        dst[kAxis0Pitch] = v[p].y;
+        dst[2 * kAxis0Pitch] = v[p].z;
+        dst[3 * kAxis0Pitch] = v[p].w;
+    }
+    __syncthreads();
+
+    const int64_t nb = a.rows / B, row_octets = a.rows / 8;
+#pragma unroll
+    for (int k = 0; k < kAxis0Cols * (kAxis0Rows / 8) / 256; ++k) {
+        const int idx = threadIdx.x + 256 * k;
+        const int cl = idx >> 5, o = idx & 31;                          // column of the tile, octet of its 256 rows
+        const float4 lo = *reinterpret_cast<const float4*>(tile + cl * kAxis0Pitch + 8 * o);
+        const float4 hi = *reinterpret_cast<const float4*>(tile + cl * kAxis0Pitch + 8 * o + 4);
+        const float x8[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        uint32_t am = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t ab = __float_as_uint(x8[i]) & 0x7fffffffu;
+            am = ab > am ? ab : am;
+        }
+        am = group_max_u32<LPB>(am);
+        const int E = block_exponent(am, a.bias, a.emax);
+        const int shift = (W - 2) - E;
         int q[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(v[o * 8 + i], shift);
-        store_stream<W>(mrow + o * W, pack8<W>(q));
+        for (int i = 0; i < 8; ++i) q[i] = quantize_one<W, RND>(x8[i], shift);
+        const int64_t col = c0 + cl, row = r0 + 8 * o;                  // rows is a multiple of B: whole blocks or none
+        if (col < a.cols && row < a.rows) {
+            store_stream<W>(a.mant + ((b * a.cols + col) * row_octets + row / 8) * W, pack8<W>(q));
+            if ((o & (LPB - 1)) == 0) a.exps[(b * a.cols + col) * nb + row / B] = (uint8_t)(E + a.bias);
+        }
     }
-    a.exps[(b * a.cols + c) * nb + rb] = (uint8_t)(E + a.bias);
 }
 
 struct DequantArgs {
@@ -349,7 +388,8 @@ mx_status launch_rows2(const QuantRows2Args& a, int rnd, hipStream_t st) {
 
 template <int W, int B>
 mx_status launch_axis0(const QuantAxis0Args& a, int rnd, hipStream_t st) {
-    dim3 grid((unsigned)ceil_div(a.cols, 256), (unsigned)(a.rows / B), (unsigned)a.batch);
+    if (ceil_div(a.cols, kAxis0Cols) > 65535) return MX_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)ceil_div(a.rows, kAxis0Rows), (unsigned)ceil_div(a.cols, kAxis0Cols), (unsigned)a.batch);
     if (rnd == MX_RNE)
         hipLaunchKernelGGL((quantize_axis0_kernel<W, B, MX_RNE>), grid, dim3(256), 0, st, a);
     else
