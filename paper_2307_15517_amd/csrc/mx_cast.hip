@@ -27,6 +27,10 @@ struct CastArgs {
     int64_t runs_per_row;      // two-row blocks: cols / 32
 };
 
+typedef short s2v __attribute__((ext_vector_type(2)));
+typedef unsigned short u2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ s2v splat(int v) { s2v r; r.x = (short)v; r.y = (short)v; return r; }
+
 template <int WS, int WD, int B, int RND>
 __global__ __launch_bounds__(256) void cast_kernel(CastArgs a) {
     constexpr int NB = B >= 32 ? 1 : 32 / B;          // blocks (or the half block) of a thread
@@ -56,9 +60,27 @@ __global__ __launch_bounds__(256) void cast_kernel(CastArgs a) {
     } else {
         for (int byte = 0; byte < n * WS / 8; ++byte) in[byte >> 2] |= (uint32_t)src[byte] << (8 * (byte & 3));
     }
-    int q[32];
+    // Two elements per register as 16-bit halves (|q| <= 128, and every intermediate of the shift below fits
+    // 16 bits), so the arithmetic runs as packed 16-bit instructions: of the four elements 4g..4g+3, pair
+    // 2g holds (4g, 4g+2) and pair 2g+1 holds (4g+1, 4g+3) -- for 8-bit sources these are the even and the
+    // odd bytes of one dword, sign-extended in place.
+    s2v pr[16];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) q[i] = stream_get<WS>(in, i * WS);
+    for (int g = 0; g < 8; ++g) {
+        if (WS == 8) {
+            const s2v x = __builtin_bit_cast(s2v, in[g]);
+            pr[2 * g] = __builtin_bit_cast(s2v, __builtin_bit_cast(u2v, in[g]) << (unsigned short)8) >> splat(8);
+            pr[2 * g + 1] = x >> splat(8);
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                s2v v;
+                v.x = (short)stream_get<WS>(in, (4 * g + p) * WS);
+                v.y = (short)stream_get<WS>(in, (4 * g + p + 2) * WS);
+                pr[2 * g + p] = v;
+            }
+        }
+    }
 
     uint32_t out[WD];
 #pragma unroll
@@ -66,13 +88,14 @@ __global__ __launch_bounds__(256) void cast_kernel(CastArgs a) {
     const int64_t blk0 = e0 / B;
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        int mx = 0;
+        constexpr int NP = BE / 2;                    // pairs of the block
+        s2v hi = pr[j * NP], lo = pr[j * NP];
 #pragma unroll
-        for (int i = 0; i < BE; ++i) {
-            const int v = q[j * BE + i];
-            const int m = v < 0 ? -v : v;
-            mx = m > mx ? m : mx;
+        for (int t = 1; t < NP; ++t) {
+            hi = __builtin_elementwise_max(hi, pr[j * NP + t]);
+            lo = __builtin_elementwise_min(lo, pr[j * NP + t]);
         }
+        int mx = max(max((int)hi.x, (int)hi.y), max(-(int)lo.x, -(int)lo.y));
         if (B == 64) {                                // lanes 2t, 2t+1 hold the halves of one block
             const int o = __builtin_amdgcn_update_dpp(0, mx, 0xB1, 0xF, 0xF, true);
             mx = o > mx ? o : mx;
@@ -84,32 +107,63 @@ __global__ __launch_bounds__(256) void cast_kernel(CastArgs a) {
             int E2 = E - (WS - 2) + (31 - __builtin_clz((unsigned)mx));
             E2 = E2 < a.emin_d ? a.emin_d : E2;
             E2 = E2 > a.emax_d ? a.emax_d : E2;
-            int sh = (E - (WS - 2)) - (E2 - (WD - 2));
+            const int sh = (E - (WS - 2)) - (E2 - (WD - 2));
             ebyte = E2 + a.bias_d;
-            // |q| <= 128: any shift beyond 16 either way gives the same result as 16
-            sh = sh > 16 ? 16 : (sh < -16 ? -16 : sh);
+            // |q| <= 128 and qmax <= 127: a left shift beyond 7 saturates every nonzero element like 7 does, a
+            // right shift beyond 9 gives zero like 9 does, and within these limits nothing leaves 16 bits
+            const int up = sh > 0 ? (sh > 7 ? 7 : sh) : 0;
+            const int k = sh < 0 ? (sh < -9 ? 9 : -sh) : 0;
+            // arithmetic right shift = floor; to nearest with ties to even: add half - 1 + (the bit that becomes
+            // the last one), then floor; toward zero: add 2^k - 1 to negatives, then floor.  k = 0 adds nothing.
+            const s2v ups = splat(up), ks = splat(k);
+            const s2v add = splat(RND == MX_RNE ? (k > 0 ? (1 << (k - 1)) - 1 : 0) : (1 << k) - 1);
+            const s2v one = splat(k > 0 ? 1 : 0);
 #pragma unroll
-            for (int i = 0; i < BE; ++i) {
-                const int v = q[j * BE + i];
-                int r;
-                if (sh >= 0) {
-                    r = v << sh;                       // |v| << 16 stays inside int32
-                } else {
-                    // arithmetic right shift = floor; to nearest with ties to even: add half - 1 + (the bit
-                    // that becomes the last one), then floor; toward zero: add 2^k - 1 to negatives, then floor
-                    const int k = -sh;
-                    if (RND == MX_RNE) r = (v + ((1 << (k - 1)) - 1) + ((v >> k) & 1)) >> k;
-                    else r = (v + ((v >> 31) & ((1 << k) - 1))) >> k;
-                }
-                r = r > qmax ? qmax : (r < -qmax ? -qmax : r);
-                const int bit = (j * BE + i) * WD;    // compile time after unrolling
-                const uint32_t code = (uint32_t)r & ((1u << WD) - 1u);
+            for (int t = 0; t < NP; ++t) {
+                const s2v v = pr[j * NP + t] << ups;
+                s2v r;
+                if (RND == MX_RNE) r = (v + add + ((v >> ks) & one)) >> ks;
+                else r = (v + ((v >> splat(15)) & add)) >> ks;
+                r = __builtin_elementwise_min(__builtin_elementwise_max(r, splat(-qmax)), splat(qmax));
+                pr[j * NP + t] = r;
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < NP; ++t) pr[j * NP + t] = splat(0);
+        }
+        // one exponent byte per block: every block of the thread, or the even lane for a block of 64
+        if (have && (B < 64 || (e0 & 63) == 0)) a.exps_out[blk0 + j] = (uint8_t)ebyte;
+    }
+    // back into the bit stream
+    if (WD == 8) {
+#pragma unroll
+        for (int g = 0; g < 8; ++g)                   // bytes: pair 2g gives 0 and 2, pair 2g+1 gives 1 and 3
+            out[g] = __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, pr[2 * g + 1]),
+                                           __builtin_bit_cast(uint32_t, pr[2 * g]), 0x06020400u);
+    } else if (WD == 4) {
+#pragma unroll
+        for (int G = 0; G < 4; ++G) {                 // eight elements per dword
+            uint32_t x[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t ev = __builtin_bit_cast(uint32_t, pr[4 * G + 2 * h]) & 0x000F000Fu;
+                const uint32_t od = __builtin_bit_cast(uint32_t, pr[4 * G + 2 * h + 1]) & 0x000F000Fu;
+                x[h] = (od << 4) | ev;                // byte 0: elements 0, 1; byte 2: elements 2, 3 of the group
+            }
+            out[G] = __builtin_amdgcn_perm(x[1], x[0], 0x06040200u);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const uint32_t c = __builtin_bit_cast(uint32_t, pr[t]) & (((1u << WD) - 1u) * 0x00010001u);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int bit = (4 * (t >> 1) + (t & 1) + 2 * h) * WD;   // compile time after unrolling
+                const uint32_t code = h == 0 ? (c & 0xFFFFu) : (c >> 16);
                 out[bit >> 5] |= code << (bit & 31);
                 if ((bit & 31) + WD > 32) out[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
             }
         }
-        // one exponent byte per block: every block of the thread, or the even lane for a block of 64
-        if (have && (B < 64 || (e0 & 63) == 0)) a.exps_out[blk0 + j] = (uint8_t)ebyte;
     }
     uint8_t* dst = a.mant_out + run * (4 * WD);
     if (n == 32) {

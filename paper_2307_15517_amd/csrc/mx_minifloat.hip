@@ -89,12 +89,12 @@ __global__ __launch_bounds__(256) void quantize_minifloat_kernel(MiniArgs a) {
                 const int L = T - cmax + 1;
                 // Rounding happens in the fp32 bit pattern.  At or above the format's smallest normal value
                 // 2^L the result keeps m fraction bits: add half of the dropped field (less one, plus the
-                // parity bit that sends a tie to the even code) and clear the field -- a carry runs into the
+                // parity bit that sends a tie to the even code) and drop the field -- a carry runs into the
                 // exponent by itself -- and the code integer c << m | f is the kept bits minus a constant.
                 // Below 2^L the step is fixed at 2^(L-m): adding 2^(L-m+23) makes the fp32 adder round to
                 // that step (ties to even), and the code integer is the low bits of the sum.
                 const int sb = 23 - m;                                          // dropped fraction bits
-                const uint32_t keep = ~((1u << sb) - 1u), half_m1 = (1u << (sb - 1)) - 1u;
+                const uint32_t half_m1 = (1u << (sb - 1)) - 1u;
                 const uint32_t code_max = (1u << (e + m)) - 1u;
                 const uint32_t rebase = (uint32_t)(126 + L) << m;               // may wrap: used modulo 2^32
                 const bool low_ok = L >= -126;                                  // 2^L is an fp32 normal
@@ -131,13 +131,12 @@ __global__ __launch_bounds__(256) void quantize_minifloat_kernel(MiniArgs a) {
                         // normal range of the format
                         uint32_t r = ab;
                         if (a.rnd == MX_RNE) r += half_m1 + (((ab >> sb) & 1u) ^ par0);
-                        uint32_t code_n = ((r & keep) >> sb) - rebase;
+                        uint32_t code_n = (r >> sb) - rebase;               // the shift drops the rounded-away field
                         // underflow range of the format
                         uint32_t code_s;
                         if (a.rnd == MX_RNE) code_s = __float_as_uint(__uint_as_float(ab) + magic) & 0x7fffffu;
                         else code_s = (uint32_t)__builtin_ldexpf(__uint_as_float(ab), m - L);   // conversion truncates
-                        code = ab < minnorm ? (low_ok ? code_s : 0u) : code_n;
-                        code = ab == 0 ? 0u : code;
+                        code = ab < minnorm ? (low_ok ? code_s : 0u) : code_n;     // zero: minnorm > 0 and code_s = 0
                     }
                     code = code > code_max ? code_max : code;                   // saturate (clamped T only)
                     out |= ((sign << (e + m)) | code) << (8 * i);
@@ -196,6 +195,12 @@ extern "C" mx_status mx_quantize_minifloat(const float* x, int64_t batch, int64_
     if (batch > 65535) return MX_ERR_UNSUPPORTED;
     MiniArgs a;
     a.x = x; a.codes = codes; a.shared = shared; a.y = nullptr;
+    // blocks never cross a row (cols % block == 0), so contiguous rows, and contiguous matrices, are one long row:
+    // no workgroup is left with the short tail of a row
+    if (row_stride == cols) {
+        cols *= rows; rows = 1; row_stride = cols;
+        if (batch_stride == cols) { cols *= batch; batch = 1; batch_stride = cols; }
+    }
     a.rows = rows; a.cols = cols; a.row_stride = row_stride; a.batch_stride = batch_stride;
     a.items_per_row = cols / 4;
     a.e = f.exp_bits; a.m = f.mant_bits; a.rnd = f.rounding;
