@@ -238,7 +238,8 @@ def linear_q(x: np.ndarray, wt: np.ndarray, bias: Optional[np.ndarray], block: i
 
 
 def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, wk: int, wp: int, wv: int,
-              scale: float, e: int = 8, rounding: int = RNE, rows: Optional[Tuple[int, int]] = None):
+              scale: float, e: int = 8, rounding: int = RNE, rows: Optional[Tuple[int, int]] = None,
+              block_rows: int = 1):
     """One head of attention with every matrix product taken in MXInt (Fig. 1: the two products of the
     attention layer have both operands quantized; Section 3.2: an emulated operator quantizes its inputs
     and computes on the quantized values; softmax itself stays in floating point).
@@ -250,25 +251,36 @@ def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, 
       4. O = MXInt product P V                                                                   [Sq,D]
     Returns O float64 [Sq,D] and a dict with the intermediate values the tests derive tolerances from:
     S, S_mag (sum_b |term_b| of step 1), P (float64), pq/pe and vq/ve (the quantized operands of step 4)
-    and O_mag.  rows=(begin,end) restricts the query rows that are computed (others are NaN)."""
+    and O_mag.  rows=(begin,end) restricts the query rows that are computed (others are NaN).
+    block_rows=2: every tensor in the paper's two-dimensional block shape (block, 2) (Section 3.1) -- two
+    neighbouring rows of the matrix that is quantized share their exponents: two queries (Q, P), two keys
+    (K), two columns of V (the rows of V^T).  pe and ve then hold one exponent row per matrix row (each
+    shared row repeated), as the product takes them."""
     Q = np.ascontiguousarray(Q, np.float32)
     K = np.ascontiguousarray(K, np.float32)
     V = np.ascontiguousarray(V, np.float32)
     r0, r1 = (0, Q.shape[0]) if rows is None else rows
-    qq, qe = quantize(Q[r0:r1], block, wq, e, rounding)
-    kq, ke = quantize(K, block, wk, e, rounding)
-    S, s_mag = gemm(qq, qe, wq, kq, ke, wk, block, e, want_mag=True)
+    R = block_rows
+    if R != 1 and (r0 % R or r1 % R):
+        raise ValueError("the row window must hold whole row groups")
+    qq, qe = quantize(Q[r0:r1], block, wq, e, rounding, block_rows=R)
+    kq, ke = quantize(K, block, wk, e, rounding, block_rows=R)
+    S, s_mag = gemm(qq, row_exps(qe, R), wq, kq, row_exps(ke, R), wk, block, e, want_mag=True)
     Z = np.float64(scale) * S
     Z = Z - Z.max(axis=1, keepdims=True)
     P = np.exp(Z)
     P = P / P.sum(axis=1, keepdims=True)
-    pq, pe = quantize(P.astype(np.float32), block, wp, e, rounding)
-    vq, ve = quantize(V, block, wv, e, rounding, axis=0)          # the quantization of V^T: [D, Sk]
+    pq, pe = quantize(P.astype(np.float32), block, wp, e, rounding, block_rows=R)
+    if R == 1:
+        vq, ve = quantize(V, block, wv, e, rounding, axis=0)      # the quantization of V^T: [D, Sk]
+    else:
+        vq, ve = quantize(np.ascontiguousarray(V.T), block, wv, e, rounding, block_rows=R)
+    pe, ve = row_exps(pe, R), row_exps(ve, R)
     Osub, o_mag = gemm(pq, pe, wp, vq, ve, wv, block, e, want_mag=True)
     O = np.full((Q.shape[0], V.shape[1]), np.nan, np.float64)
     O[r0:r1] = Osub
     return O, {"S": S, "S_mag": s_mag, "P": P, "pq": pq, "pe": pe, "vq": vq, "ve": ve, "O_mag": o_mag,
-               "rows": (r0, r1)}
+               "rows": (r0, r1), "block_rows": R}
 
 
 def quantize_minifloat(x: np.ndarray, block: int, e: int, m: int, rounding: int = RNE) -> Tuple[np.ndarray, np.ndarray]:

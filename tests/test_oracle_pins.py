@@ -626,6 +626,55 @@ def test_attention_steps_against_library_routines():
     assert np.array_equal(O2[8:16], O[8:16]) and np.all(np.isnan(O2[:8])) and np.all(np.isnan(O2[16:]))
 
 
+def test_attention_two_row_blocks_pairs_of_equal_rows_change_nothing():
+    """The paper's block shape (block, 2) (Section 3.1) in the attention layer.  When rows 2i and 2i+1 of
+    every quantized matrix are equal (queries, keys, and the columns of V, which are the rows of V^T), a
+    two-row block holds the same values twice, so its maximum, exponent and mantissas are those of the
+    one-row blocks: the outputs are identical."""
+    rng = np.random.default_rng(11)
+    Sq, Sk, D = 12, 32, 32
+    Q = np.repeat(rng.standard_normal((Sq // 2, D)), 2, axis=0).astype(np.float32)
+    K = np.repeat(rng.standard_normal((Sk // 2, D)) * np.exp2(rng.integers(-3, 4, (Sk // 2, 1))), 2, axis=0).astype(np.float32)
+    V = np.repeat(rng.standard_normal((Sk, D // 2)) * np.exp2(rng.integers(-3, 4, (1, D // 2))), 2, axis=1).astype(np.float32)
+    O1, i1 = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=0.4)
+    O2, i2 = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=0.4, block_rows=2)
+    assert np.array_equal(O1, O2) and np.array_equal(i1["pq"], i2["pq"]) and np.array_equal(i1["pe"], i2["pe"])
+    assert np.array_equal(i1["vq"], i2["vq"]) and np.array_equal(i1["ve"], i2["ve"])
+    # ordinary inputs: the exponent of the pair (2i, 2i+1) is the larger of the two rows' own exponents
+    # (floor(log2) of the larger maximum), for the probabilities and for V^T
+    Q, K, V = (rng.standard_normal(x.shape).astype(np.float32) for x in (Q, K, V))
+    _, j1 = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=0.4)
+    _, j2 = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=0.4, block_rows=2)
+    for key in ("pe", "ve"):
+        pair_max = np.maximum(j1[key][0::2], j1[key][1::2])
+        assert np.array_equal(j2[key][0::2], pair_max) and np.array_equal(j2[key][1::2], pair_max)
+        assert not np.array_equal(j1[key], j2[key])
+
+
+def test_attention_two_row_blocks_hand_worked():
+    """Query 0 matches key 0 by a wide margin (P = 1, 0, 0, ...), query 1 is zero (P = 1/16 each), ternary
+    probabilities (width 2: one step = 2^E).  One-row blocks: row 1 has E = -4, mantissa 1 everywhere, and its
+    output is the mean of the quantized V.  Two-row blocks: rows 0 and 1 share E = 0 from the 1 in row 0, so
+    row 1's 1/16 is far below half a step and quantizes to 0: its output is exactly 0, row 0 is unchanged."""
+    Sk, D = 16, 16
+    rng = np.random.default_rng(12)
+    K = np.zeros((Sk, D), np.float32)
+    K[0, 0] = 1.0
+    Q = np.zeros((2, D), np.float32)
+    Q[0, 0] = 2000.0
+    V = rng.standard_normal((Sk, D)).astype(np.float32)
+    vd = _vdeq(V, 16, 8)
+    O1, i1 = orc.attention(Q, K, V, 16, 8, 8, 2, 8, scale=1.0)
+    assert i1["pq"][1].tolist() == [1] * 16 and i1["pe"][1, 0] == 127 - 4
+    assert np.array_equal(O1[0], vd[0]) and np.array_equal(O1[1], vd.sum(axis=0) / 16)
+    O2, i2 = orc.attention(Q, K, V, 16, 8, 8, 2, 8, scale=1.0, block_rows=2)
+    assert i2["pe"][:, 0].tolist() == [127, 127] and i2["pq"][1].tolist() == [0] * 16
+    # V^T in two-row blocks: columns 2j and 2j+1 of V share exponents, row 0 of the output is that V row 0
+    vq, ve = orc.quantize(np.ascontiguousarray(V.T), 16, 8, block_rows=2)
+    vd2 = orc.dequantize(vq, orc.row_exps(ve, 2), 16, 8).T
+    assert np.array_equal(O2[0], vd2[0]) and np.all(O2[1] == 0.0)
+
+
 # ----------------------------------------------------------------------------------------------
 # Block Minifloat and Block Logarithm (Section 2): the format's value set written out, brute force
 # ----------------------------------------------------------------------------------------------
