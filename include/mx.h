@@ -276,8 +276,12 @@ MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const
  * accumulation error of S times scale); a probability that close to a rounding tie of the quantizer,
  * or a block maximum that close to a power of two, can take the neighbouring mantissa or exponent.
  * Blocks of P^ whose elements are below 2^-126 count as zero.
- * Built for MX_LAYOUT_MATRIX with blocks of 16 (block_rows 1) in all four formats and D <= 128;
- * anything else is MX_ERR_UNSUPPORTED.
+ * Two-row blocks (block_rows = 2, the paper's own block shape, Section 3.1) are taken for every tensor:
+ * the packed operands carry their exponents inside the elements, so fq, fk, fv only need sizes that
+ * hold whole pairs (Sq for Q, Sk for K, D for V^T); with fp.block_rows = 2 (Sq even) queries 2t and
+ * 2t+1 share the exponent of each block of 16 probabilities.
+ * Built for MX_LAYOUT_MATRIX with blocks of 16 in all four formats and D <= 128; anything else is
+ * MX_ERR_UNSUPPORTED.
  */
 MX_API mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t D, const void* Q_packed, mx_format fq,
                        const void* K_packed, mx_format fk, const void* Vt_packed, mx_format fv, mx_format fp,

@@ -49,6 +49,7 @@ struct AttnArgs {
     float c;                       // scale * log2(e)
     int32_t wp, bias_p, emax_p;
     int32_t vec;                   // O rows may be stored as float4
+    float pair;                    // 0 when two neighbouring queries share the exponents of P, else -inf
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_addr + 16*L.
@@ -280,6 +281,10 @@ __global__ __launch_bounds__(256, RQ == 1 ? 2 : 1) void attention_bf16_kernel(At
                             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(sm), __float_as_uint(sm), false, false);
                             sm = __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
                             float m = __builtin_fmaf(sm, c, -mrow[q]);
+                            // two-row blocks: queries 2t and 2t+1 (neighbouring lanes) share the exponent, the larger
+                            // of the two log-probabilities; one-row blocks add -inf to the neighbour's and keep their own
+                            m = __builtin_fmaxf(m, g.pair + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                                                                0, __builtin_bit_cast(int, m), 0xB1, 0xF, 0xF, true)));
                             m = __builtin_fmaxf(m, -200.f);                   // also for all keys masked, or c = 0 with them
                             int E = (int)__builtin_floorf(m);
                             E = E < -g.bias_p ? -g.bias_p : E;
@@ -448,13 +453,16 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
     if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
     if (batch < 0 || Sq < 0 || Sk < 1 || D < 1 || D % fq.block != 0 || Sk % fp.block != 0 || ldo < D) return MX_ERR_BAD_ARG;
     if (!(scale == scale) || __builtin_isinf(scale)) return MX_ERR_BAD_ARG;
-    // built for the bfloat16 form of the matrix layout: blocks of 16 (one row each) in all four formats
+    // two-row blocks: whole pairs of queries (Q, P), of keys (K), of columns of V (the rows of V^T)
+    if (((fq.block_rows == 2 || fp.block_rows == 2) && Sq % 2 != 0) || (fk.block_rows == 2 && Sk % 2 != 0) ||
+        (fv.block_rows == 2 && D % 2 != 0))
+        return MX_ERR_BAD_ARG;
+    // built for the bfloat16 form of the matrix layout: blocks of 16 in all four formats.  The packed operands carry
+    // their exponents inside the elements, so their block shape (one or two rows) makes no difference here; P's does.
     if (layout != MX_LAYOUT_MATRIX || !matrix_format_ok(fq) || !matrix_format_ok(fk) || !matrix_format_ok(fv) ||
         !matrix_format_ok(fp))
         return MX_ERR_UNSUPPORTED;
-    if (fq.block != 16 || fp.block != 16 || fq.block_rows != 1 || fk.block_rows != 1 || fv.block_rows != 1 ||
-        fp.block_rows != 1 || D > 128)
-        return MX_ERR_UNSUPPORTED;
+    if (fq.block != 16 || fp.block != 16 || D > 128) return MX_ERR_UNSUPPORTED;
     if (batch == 0 || Sq == 0) return MX_OK;
     if (!Q_packed || !K_packed || !Vt_packed || !O) return MX_ERR_BAD_ARG;
     if (((uintptr_t)Q_packed & 255) || ((uintptr_t)K_packed & 255) || ((uintptr_t)Vt_packed & 255)) return MX_ERR_BAD_ARG;
@@ -470,6 +478,7 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
     g.wp = fp.mant_bits; g.bias_p = (1 << (fp.exp_bits - 1)) - 1;
     g.emax_p = ((1 << fp.exp_bits) - 1) - g.bias_p;
     g.vec = (((uintptr_t)O & 15) == 0 && ldo % 4 == 0 && o_batch_stride % 4 == 0) ? 1 : 0;
+    g.pair = fp.block_rows == 2 ? 0.f : -__builtin_inff();
     const int dt = (int)ceil_div(D, 32);
     hipStream_t st = (hipStream_t)stream;
     if (gq.ksteps == 2)

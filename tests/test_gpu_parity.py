@@ -941,8 +941,11 @@ def attention_bound(info, wp, wv, scale, rounding, e=8, block=16):
     if rounding == orc.RTZ:
         may &= x >= 0.5                                                      # nothing below zero to fall to
     amax = P.reshape(R, -1, block).max(axis=2)
-    frac = amax / np.ldexp(1.0, E)                                           # in [1, 2) unless the exponent is clamped
     eps_b = eps.reshape(R, -1, block).max(axis=2)
+    if info.get("block_rows", 1) == 2:                                       # the block spans rows 2t and 2t+1
+        amax = np.repeat(np.maximum(amax[0::2], amax[1::2]), 2, axis=0)
+        eps_b = np.repeat(np.maximum(eps_b[0::2], eps_b[1::2]), 2, axis=0)
+    frac = amax / np.ldexp(1.0, E)                                           # in [1, 2) unless the exponent is clamped
     amb = ((np.abs(frac - 1.0) <= 2 * eps_b) | (np.abs(frac - 2.0) <= 4 * eps_b)) & (amax > 0)
     dev_ = np.where(may, step, 0.0) + np.repeat(np.where(amb, 2.0, 0.0), block, axis=1) * step
     vabs = np.abs(orc.dequantize(info["vq"], info["ve"], block, wv, e)).T    # [Sk, D]
@@ -951,17 +954,21 @@ def attention_bound(info, wp, wv, scale, rounding, e=8, block=16):
     return bound, float(may.mean() + amb.mean())
 
 
-def run_attention(Q, K, V, widths, scale, heads_checked=None, rows=None, rounding=mx.MX_RNE, e_pv=8, max_maybe=1e-2):
+def run_attention(Q, K, V, widths, scale, heads_checked=None, rows=None, rounding=mx.MX_RNE, e_pv=8, max_maybe=1e-2,
+                  block_rows=1):
     """Q [H,Sq,D], K, V [H,Sk,D] float32 numpy.  Returns the worst error as a fraction of its bound."""
     wq, wk, wp, wv = widths
     H, Sq, D = Q.shape
     Sk = K.shape[1]
-    fq, fk = mx.fmt(16, wq, 8, rounding), mx.fmt(16, wk, 8, rounding)
-    fp_, fv = mx.fmt(16, wp, e_pv, rounding), mx.fmt(16, wv, e_pv, rounding)
+    fq, fk = mx.fmt(16, wq, 8, rounding, block_rows), mx.fmt(16, wk, 8, rounding, block_rows)
+    fp_, fv = mx.fmt(16, wp, e_pv, rounding, block_rows), mx.fmt(16, wv, e_pv, rounding, block_rows)
     A = mx.quantize_pack(dev(Q), fq, MAT)
     B = mx.quantize_pack(dev(K), fk, MAT)
-    vm, ve = mx.quantize(dev(V), fv, axis=0)                                 # canonical form of V^T
-    Bv = mx.pack(vm, ve, H, D, Sk, fv, MAT)
+    if block_rows == 1:
+        vm, ve = mx.quantize(dev(V), fv, axis=0)                             # canonical form of V^T
+        Bv = mx.pack(vm, ve, H, D, Sk, fv, MAT)
+    else:                                                                    # two columns of V share exponents
+        Bv = mx.quantize_pack(dev(np.ascontiguousarray(V.transpose(0, 2, 1))), fv, MAT)
     O = torch.full((H, Sq, D + 4), 7.0, dtype=torch.float32, device=DEV)     # row pitch > D: the gap must survive
     mx.mx_attention(H, Sq, Sk, D, A, fq, B, fk, Bv, fv, fp_, scale, MAT, O, D + 4, Sq * (D + 4))
     torch.cuda.synchronize()
@@ -970,7 +977,7 @@ def run_attention(Q, K, V, widths, scale, heads_checked=None, rows=None, roundin
     worst = 0.0
     for hd in (range(H) if heads_checked is None else heads_checked):
         # the oracle re-quantizes V with exp_bits e_pv; Q and K keep 8 exponent bits
-        o_ref, info = orc_attention(Q[hd], K[hd], V[hd], wq, wk, wp, wv, scale, e_pv, rounding, rows)
+        o_ref, info = orc_attention(Q[hd], K[hd], V[hd], wq, wk, wp, wv, scale, e_pv, rounding, rows, block_rows)
         r0, r1 = info["rows"]
         bound, maybe = attention_bound(info, wp, wv, scale, rounding, e_pv)
         assert maybe < max_maybe, "the tolerance would excuse too many mantissas (%.3g)" % maybe
@@ -984,11 +991,12 @@ def run_attention(Q, K, V, widths, scale, heads_checked=None, rows=None, roundin
     return worst
 
 
-def orc_attention(Q, K, V, wq, wk, wp, wv, scale, e_pv, rounding, rows):
+def orc_attention(Q, K, V, wq, wk, wp, wv, scale, e_pv, rounding, rows, block_rows=1):
     """orc.attention with a separate exponent width for P and V (the oracle function takes one width for
     all four tensors; with 8 bits everywhere this is the same call)."""
     if e_pv == 8:
-        return orc.attention(Q, K, V, 16, wq, wk, wp, wv, scale, 8, rounding, rows)
+        return orc.attention(Q, K, V, 16, wq, wk, wp, wv, scale, 8, rounding, rows, block_rows)
+    assert block_rows == 1
     r0, r1 = (0, Q.shape[0]) if rows is None else rows
     qq, qe = orc.quantize(Q[r0:r1], 16, wq, 8, rounding)
     kq, ke = orc.quantize(K, 16, wk, 8, rounding)
@@ -1050,6 +1058,24 @@ def test_attention_fused_peaked_and_flat_rows():
     say("worst/bound", run_attention(Q, K, V, (8, 8, 7, 8), 1.0, max_maybe=0.6))
 
 
+@pytest.mark.parametrize("Sq,Sk,dim,widths", [(300, 272, 128, (8, 8, 6, 5)), (34, 48, 32, (7, 6, 5, 3)),
+                                               (130, 2080, 64, (8, 4, 8, 8)), (2, 16, 16, (8, 8, 2, 4))])
+def test_attention_fused_two_row_blocks(Sq, Sk, dim, widths):
+    """Every tensor in the paper's block shape (16, 2) (Section 3.1): pairs of queries share the exponents of
+    Q and of the probabilities, pairs of keys those of K, pairs of columns those of V.  Row scales differ
+    from query to query, so the pair's exponent is often set by the neighbour."""
+    rng = np.random.default_rng(Sq + Sk)
+    Q = (rng.standard_normal((2, Sq, dim)) * rng.choice([0.2, 1.0, 4.0], size=(2, Sq, 1))).astype(np.float32)
+    K = rng.standard_normal((2, Sk, dim)).astype(np.float32)
+    V = (rng.standard_normal((2, Sk, dim)) * rng.choice([0.01, 1.0, 30.0], size=(2, 1, dim))).astype(np.float32)
+    for rounding in (mx.MX_RNE, mx.MX_RTZ):
+        say("worst/bound", run_attention(Q, K, V, widths, dim ** -0.5, rounding=rounding, block_rows=2))
+    # and it is not the one-row result: the exponents of P differ
+    _, i1 = orc.attention(Q[0], K[0], V[0], 16, *widths, dim ** -0.5)
+    _, i2 = orc.attention(Q[0], K[0], V[0], 16, *widths, dim ** -0.5, block_rows=2)
+    assert not np.array_equal(i1["pe"], i2["pe"])
+
+
 def test_attention_fused_full_size_sampled_heads_and_rows():
     """32 heads x 2048 x 2048 x 128, widths of seed 0, in the launch the benchmark times; the oracle takes two
     heads and a window of query rows each."""
@@ -1076,7 +1102,10 @@ def test_attention_rejections():
     assert call(fq=mx.fmt(32, 4), fk=mx.fmt(32, 4), D=128) == mx.MX_ERR_UNSUPPORTED
     assert call(layout=mx.MX_LAYOUT_FRAGMENT) == mx.MX_ERR_UNSUPPORTED
     assert call(D=256, ldo=256) == mx.MX_ERR_UNSUPPORTED
-    assert call(fp_=mx.fmt(16, 8, block_rows=2), fv=mx.fmt(16, 8, block_rows=2)) == mx.MX_ERR_UNSUPPORTED
+    f2 = mx.fmt(16, 8, block_rows=2)
+    assert call(fp_=f2, fv=f2) == mx.MX_OK                 # two-row blocks: whole pairs of queries
+    assert call(Sq=63, fp_=f2) == mx.MX_ERR_BAD_ARG
+    assert call(Sq=63, fq=f2) == mx.MX_ERR_BAD_ARG
     assert call(Sq=0) == mx.MX_OK
     torch.cuda.synchronize()
 
