@@ -212,7 +212,9 @@ MX_API mx_status mx_quantize_pack(const float* x, int64_t batch, int64_t rows, i
  * that mx_quantize (axis 0) produces.  This is how the V operand of P V is prepared (V [keys x d] is
  * reduced over the keys: Fig. 1, and mx_attention's Vt_packed).  rows must be a multiple of f.block.
  * Same pointer rules as mx_quantize_pack; `packed` holds mx_packed_bytes(batch, cols, rows, f, layout)
- * bytes.  Built for MX_LAYOUT_MATRIX with blocks of 16 (block_rows 1); else MX_ERR_UNSUPPORTED.
+ * bytes.  With f.block_rows = 2 (cols even) columns 2p and 2p+1 of x, the rows of the operand, share
+ * their exponents: the bytes of mx_quantize_pack on the transposed matrix.
+ * Built for MX_LAYOUT_MATRIX with blocks of 16; else MX_ERR_UNSUPPORTED.
  */
 MX_API mx_status mx_quantize_pack_axis0(const float* x, int64_t batch, int64_t rows, int64_t cols,
                                         int64_t row_stride, int64_t batch_stride, mx_format f, int32_t layout,

@@ -186,7 +186,7 @@ extern "C" mx_status mx_quantize_pack_axis0(const float* x, int64_t batch, int64
     if (s != MX_OK) return s;
     if (row_stride < cols) return MX_ERR_BAD_ARG;
     if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
-    if (layout != MX_LAYOUT_MATRIX || f.block != 16 || f.block_rows != 1) return MX_ERR_UNSUPPORTED;
+    if (layout != MX_LAYOUT_MATRIX || f.block != 16) return MX_ERR_UNSUPPORTED;
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!x || !packed || ((uintptr_t)x & 3) || ((uintptr_t)packed & 255)) return MX_ERR_BAD_ARG;
     if (batch > 65535) return MX_ERR_UNSUPPORTED;

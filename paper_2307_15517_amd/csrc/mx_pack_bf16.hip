@@ -194,6 +194,7 @@ struct BfQPackTArgs {
     BfGeom g;                                          // of the operand: cols x rows
     int32_t bias, emax;
     int32_t vec;                                       // 16-byte loads are aligned
+    int32_t brows;                                     // 2: columns 2p and 2p+1 of x (rows of the operand) share exponents
 };
 
 constexpr int kBfTPitch = 128 + 4;     // floats per LDS tile row: the two lane halves (8 rows apart) land 32 banks apart
@@ -247,6 +248,10 @@ __global__ __launch_bounds__(256) void quantize_pack_bf16_axis0_kernel(BfQPackTA
         }
         const uint32_t o = (uint32_t)__shfl_xor((int)am, 32, 64);
         am = o > am ? o : am;
+        if (a.brows == 2) {             // two-row blocks: the neighbouring lane holds the neighbouring column of x
+            const uint32_t o2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)am, 0xB1, 0xF, 0xF, true);
+            am = o2 > am ? o2 : am;
+        }
         const int ef = (int)(am >> 23);
         int E = ef == 0 ? -127 : ef - 127;
         E = E < -a.bias ? -a.bias : E;
@@ -331,6 +336,7 @@ mx_status quantize_pack_bf16_axis0(const float* x, int64_t batch, int64_t rows, 
     a.bias = (1 << (f.exp_bits - 1)) - 1;
     a.emax = ((1 << f.exp_bits) - 1) - a.bias;
     a.vec = (((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0 && (batch_stride & 3) == 0) ? 1 : 0;
+    a.brows = f.block_rows;
     if (a.g.ksteps / 2 > 0x7fffffffLL || ceil_div(a.g.row_tiles, 4) > 65535) return MX_ERR_UNSUPPORTED;
     switch (f.mant_bits) {
         case 2: return launch_bf_qpack_t<2>(a, batch, f.rounding, st);

@@ -968,7 +968,8 @@ def run_attention(Q, K, V, widths, scale, heads_checked=None, rows=None, roundin
         vm, ve = mx.quantize(dev(V), fv, axis=0)                             # canonical form of V^T
         Bv = mx.pack(vm, ve, H, D, Sk, fv, MAT)
     else:                                                                    # two columns of V share exponents
-        Bv = mx.quantize_pack(dev(np.ascontiguousarray(V.transpose(0, 2, 1))), fv, MAT)
+        Bv = torch.empty((mx.mx_packed_bytes(H, D, Sk, fv, MAT),), dtype=torch.uint8, device=DEV)
+        mx.mx_quantize_pack_axis0(dev(V), H, Sk, D, D, Sk * D, fv, MAT, Bv)
     O = torch.full((H, Sq, D + 4), 7.0, dtype=torch.float32, device=DEV)     # row pitch > D: the gap must survive
     mx.mx_attention(H, Sq, Sk, D, A, fq, B, fk, Bv, fv, fp_, scale, MAT, O, D + 4, Sq * (D + 4))
     torch.cuda.synchronize()
@@ -1211,6 +1212,32 @@ def test_quantize_pack_axis0_equals_quantize_then_pack(rows, cols, w, rounding, 
         oq, oe = orc.quantize(x[b, :, :cols], 16, w, e, rounding, axis=0)
         assert np.array_equal(host(um).reshape(batch, -1)[b], orc.pack_bits(oq, w).reshape(-1))
         assert np.array_equal(host(ue).reshape(batch, -1)[b], oe.reshape(-1))
+
+
+@pytest.mark.parametrize("rows,cols,w,rounding", [(64, 128, 8, mx.MX_RNE), (272, 96, 3, mx.MX_RTZ), (2080, 130, 6, mx.MX_RNE),
+                                                   (16, 2, 4, mx.MX_RNE)])
+def test_quantize_pack_axis0_two_row_blocks(rows, cols, w, rounding):
+    """Blocks of (16 keys, 2 columns): the bytes of mx_quantize_pack on the transposed matrix with two-row
+    blocks, and the canonical form recovered by mx_unpack is the oracle's quantization of x^T."""
+    rng = np.random.default_rng(rows * 7 + cols)
+    batch = 2
+    x = (rng.standard_normal((batch, rows, cols)) * np.exp2(rng.integers(-10, 10, size=(batch, 1, cols)))).astype(np.float32)
+    x[0, :16, :2] = 0.0
+    f = mx.fmt(16, w, 8, rounding, block_rows=2)
+    want = mx.quantize_pack(dev(np.ascontiguousarray(x.transpose(0, 2, 1))), f, MAT)
+    got = torch.full((mx.mx_packed_bytes(batch, cols, rows, f, MAT),), 0x5A, dtype=torch.uint8, device=DEV)
+    mx.mx_quantize_pack_axis0(dev(x), batch, rows, cols, cols, rows * cols, f, MAT, got)
+    torch.cuda.synchronize()
+    valid = ((cols + 31) // 32) * (((rows + 31) // 32 + 1) // 2 * 2) * 2048 + cols * (rows // 16)
+    per = mx.mx_packed_bytes(1, cols, rows, f, MAT)
+    assert torch.equal(got.view(batch, per)[:, :valid], want.view(batch, per)[:, :valid])
+    um, ue = mx.unpack(got, batch, cols, rows, f, MAT)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        oq, oe = orc.quantize(np.ascontiguousarray(x[b].T), 16, w, 8, rounding, block_rows=2)
+        assert np.array_equal(host(um).reshape(batch, -1)[b], orc.pack_bits(oq, w).reshape(-1))
+        assert np.array_equal(host(ue).reshape(batch, -1)[b], oe.reshape(-1))
+    assert mx.mx_quantize_pack_axis0(dev(x), batch, rows, cols - 1, cols, rows * cols, f, MAT, got, check=False) == mx.MX_ERR_BAD_ARG
 
 
 def test_quantize_pack_axis0_workload_and_rejections():
