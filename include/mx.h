@@ -60,9 +60,9 @@ typedef struct {
                           paper's block shape -- MXInt((16,2),8,7) is block 16, block_rows 2, mant_bits 8.
                           With 2, rows must be even and the canonical exponent array is
                           [rows/2][cols/block]; the packed layouts repeat the byte for both rows, so
-                          mx_gemm does not care.  Not supported (MX_ERR_UNSUPPORTED): mx_quantize along
-                          axis 0, mx_cast unless cols is a multiple of 32, and the activation format of
-                          mx_linear. */
+                          mx_gemm does not care (along axis 0 the rows are those of the transposed
+                          matrix: two columns of x).  Not supported (MX_ERR_UNSUPPORTED): mx_cast
+                          unless cols is a multiple of 32. */
 } mx_format;
 
 enum { MX_RNE = 0,  /* round to nearest, ties to the even mantissa */
@@ -296,6 +296,7 @@ MX_API mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t D, 
  * A_scratch: device buffer of mx_packed_bytes(1, M, K, fx, layout) bytes, 256-byte
  * aligned, for the packed activations (caller-owned, may be reused; its content after the call is
  * unspecified: for one or two rows the kernel quantizes straight into on-chip memory).
+ * fx.block_rows = 2 (rows 2p and 2p+1 of x share their exponents) needs an even M.
  */
 MX_API mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
                     void* A_scratch, const void* B_packed, int64_t N, mx_format fb, int32_t layout,

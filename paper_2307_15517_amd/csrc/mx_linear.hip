@@ -206,7 +206,8 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
                                int32_t layout, float* Y, int64_t ldy, void* stream) {
     if (!format_ok_quant(fx) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
     if (fx.block != fb.block || fx.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
-    if (!format_ok_gemm(fx) || fx.block_rows != 1) return MX_ERR_UNSUPPORTED;
+    if (!format_ok_gemm(fx)) return MX_ERR_UNSUPPORTED;
+    if (fx.block_rows == 2 && M % 2 != 0) return MX_ERR_BAD_ARG;      // rows 2p and 2p+1 share their exponents
     if (layout != MX_LAYOUT_FRAGMENT) return layout == MX_LAYOUT_MATRIX ? MX_ERR_UNSUPPORTED : MX_ERR_BAD_ARG;
     if (M < 0 || N < 0 || K < 0 || K % fx.block != 0 || row_stride < K || ldy < N) return MX_ERR_BAD_ARG;
     if (M > 8) return MX_ERR_UNSUPPORTED;
@@ -214,7 +215,7 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
     if (K > 0 && (!x || !A_scratch || !B_packed)) return MX_ERR_BAD_ARG;
     if (((uintptr_t)x & 3) || ((uintptr_t)A_scratch & 255)) return MX_ERR_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if (K > 0 && M <= 2 && ((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0) {
+    if (K > 0 && M <= 2 && fx.block_rows == 1 && ((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0) {
         // one launch: the dot-product decode kernel quantizes the activations on its way into LDS
         // (same arithmetic, same accumulation order as the two-launch form); A_scratch is not touched
         const GemmArgs g = fragment_args(M, N, K, A_scratch, fx, B_packed, fb, Y, ldy, M * ldy);

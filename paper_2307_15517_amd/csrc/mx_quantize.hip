@@ -244,6 +244,7 @@ struct QuantAxis0Args {
     uint8_t* exps;
     int64_t batch, rows, cols, row_stride, batch_stride;
     int32_t bias, emax;
+    int32_t brows;             // 2: columns 2p and 2p+1 (rows 2p, 2p+1 of the transposed matrix) share exponents
 };
 
 // Blocks down the rows of each column; the output is the canonical form of the transposed
@@ -304,6 +305,10 @@ __global__ __launch_bounds__(256) void quantize_axis0_kernel(QuantAxis0Args a) {
             am = ab > am ? ab : am;
         }
         am = group_max_u32<LPB>(am);
+        if (a.brows == 2) {             // the two halves of a wave hold the same octets of columns 2p and 2p+1
+            const uint32_t other = (uint32_t)__shfl_xor((int)am, 32, 64);
+            am = other > am ? other : am;
+        }
         const int E = block_exponent(am, a.bias, a.emax);
         const int shift = (W - 2) - E;
         int q[8];
@@ -312,7 +317,8 @@ __global__ __launch_bounds__(256) void quantize_axis0_kernel(QuantAxis0Args a) {
         const int64_t col = c0 + cl, row = r0 + 8 * o;                  // rows is a multiple of B: whole blocks or none
         if (col < a.cols && row < a.rows) {
             store_stream<W>(a.mant + ((b * a.cols + col) * row_octets + row / 8) * W, pack8<W>(q));
-            if ((o & (LPB - 1)) == 0) a.exps[(b * a.cols + col) * nb + row / B] = (uint8_t)(E + a.bias);
+            if ((o & (LPB - 1)) == 0 && (col & (a.brows - 1)) == 0)
+                a.exps[(b * (a.cols / a.brows) + col / a.brows) * nb + row / B] = (uint8_t)(E + a.bias);
         }
     }
 }
@@ -449,8 +455,7 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
     if (batch < 0 || rows < 0 || cols < 0 || row_stride < cols) return MX_ERR_BAD_ARG;
     if (axis != 0 && axis != 1) return MX_ERR_BAD_ARG;
     if ((axis == 1 ? cols : rows) % f.block != 0) return MX_ERR_BAD_ARG;
-    if (f.block_rows == 2 && axis == 1 && rows % 2 != 0) return MX_ERR_BAD_ARG;
-    if (f.block_rows == 2 && axis == 0) return MX_ERR_UNSUPPORTED;
+    if (f.block_rows == 2 && (axis == 1 ? rows : cols) % 2 != 0) return MX_ERR_BAD_ARG;
     if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!x || !mant || !exps) return MX_ERR_BAD_ARG;
@@ -485,7 +490,7 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
         a.x = x; a.mant = mant; a.exps = exps;
         a.batch = batch; a.rows = rows; a.cols = cols;
         a.row_stride = row_stride; a.batch_stride = batch_stride;
-        a.bias = bias; a.emax = emax;
+        a.bias = bias; a.emax = emax; a.brows = f.block_rows;
         MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_axis0<kW, kB>(a, f.rounding, st))));
     }
     return MX_ERR_UNSUPPORTED;

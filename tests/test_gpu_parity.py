@@ -111,6 +111,21 @@ def test_quantize_axis0(block, w):
     check_quantize(x, block, w, axis=0)
 
 
+@pytest.mark.parametrize("block,w,cols", [(16, 4, 130), (16, 8, 32), (32, 5, 66), (8, 3, 2), (64, 6, 34)])
+def test_quantize_axis0_two_row_blocks(block, w, cols):
+    """Blocks of (block rows of x, 2 columns): the canonical form of the transposed matrix with two-row blocks."""
+    rng = np.random.default_rng(177 + w)
+    x = special_values(rng, 5 * 64, cols)                # 320 rows: two row tiles of the kernel, the second ragged
+    x[:, 1::2] *= np.exp2(rng.integers(-6, 1, size=(1, cols // 2))).astype(np.float32)   # neighbours of unequal size
+    for rounding in (mx.MX_RNE, mx.MX_RTZ):
+        f = mx.fmt(block, w, 8, rounding, block_rows=2)
+        mant, exps = mx.quantize(dev(x), f, axis=0)
+        torch.cuda.synchronize()
+        q, ex = orc.quantize(np.ascontiguousarray(x.T), block, w, 8, rounding, block_rows=2)
+        assert np.array_equal(host(exps), ex.reshape(-1)), "exponent bytes differ"
+        assert np.array_equal(host(mant), orc.pack_bits(q, w).reshape(-1)), "mantissa bytes differ"
+
+
 def test_quantize_workload_shapes():
     """The activation tensors of the LLM-shaped workloads at full size."""
     for case in inputs.single_linear() + inputs.opt125m_layer() + inputs.llama7b_prefill()[:1] + \
@@ -237,13 +252,13 @@ def test_two_row_blocks_rejections():
     xf = torch.zeros((8, 64), dtype=torch.float32, device=DEV)
     out = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
     assert mx.mx_quantize(xf, 1, 7, 64, 64, 0, 1, f2, buf, out, check=False) == mx.MX_ERR_BAD_ARG          # odd rows
-    assert mx.mx_quantize(xf, 1, 32, 16, 16, 0, 0, f2, buf, out, check=False) == mx.MX_ERR_UNSUPPORTED     # along the rows
+    assert mx.mx_quantize(xf, 1, 32, 15, 16, 0, 0, f2, buf, out, check=False) == mx.MX_ERR_BAD_ARG         # along the rows: odd columns
     assert mx.mx_cast(buf, buf, 1, 8, 48, f2, mx.fmt(16, 4, block_rows=2), out, out, check=False) == mx.MX_ERR_UNSUPPORTED   # cols % 32
     assert mx.mx_cast(buf, buf, 1, 8, 64, f2, mx.fmt(16, 4), out, out, check=False) == mx.MX_ERR_BAD_ARG                     # block_rows differ
     assert mx.mx_quantize(xf, 1, 8, 64, 64, 0, 1, mx.fmt(16, 8, block_rows=3), buf, out, check=False) == mx.MX_ERR_BAD_ARG
     y = torch.zeros((2, 64), dtype=torch.float32, device=DEV)
-    assert mx.mx_linear(xf, 2, 64, 64, f2, buf, buf, 64, mx.fmt(16, 4), mx.MX_LAYOUT_FRAGMENT, y, 64,
-                        check=False) == mx.MX_ERR_UNSUPPORTED
+    assert mx.mx_linear(xf, 1, 64, 64, f2, buf, buf, 64, mx.fmt(16, 4), mx.MX_LAYOUT_FRAGMENT, y, 64,
+                        check=False) == mx.MX_ERR_BAD_ARG                                                  # odd rows
     assert mx.mx_exps_bytes(1, 8, 64, f2) == 4 * 4 and mx.mx_exps_bytes(1, 7, 64, f2) == 0
 
 
@@ -449,6 +464,27 @@ def test_linear_rows_3_to_8_formats_and_alignment(block, wx, ww, M, e, rounding)
         assert torch.equal(y1, y2)
         y_ref, mag = orc.linear(xpad[:, off:off + K], wt, block, wx, ww, e, rounding, want_mag=True)
         check_product(host(y2), y_ref, mag, "linear block %d off %d" % (block, off))
+
+
+@pytest.mark.parametrize("M,block,wx,ww", [(2, 16, 8, 4), (4, 16, 8, 4), (8, 32, 6, 5), (6, 64, 8, 8)])
+def test_linear_two_row_activation_blocks(M, block, wx, ww):
+    """mx_linear with the paper's (block, 2) shape for the activations (rows 2p and 2p+1 of x share their
+    exponents) and for the weights: the oracle's product of the two-row quantizations."""
+    rng = np.random.default_rng(block + M)
+    K, N = 9 * block, 100
+    x = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-6, 7, size=(M, 1)))).astype(np.float32)
+    wt = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    fa, fb = mx.fmt(block, wx, block_rows=2), mx.fmt(block, ww, block_rows=2)
+    B = mx.quantize_pack(dev(wt), fb, mx.MX_LAYOUT_FRAGMENT)
+    scratch = torch.zeros(mx.mx_packed_bytes(1, M, K, fa), dtype=torch.uint8, device=DEV)
+    y = torch.full((M, N), 3.0, dtype=torch.float32, device=DEV)
+    mx.mx_linear(dev(x), M, K, K, fa, scratch, B, N, fb, mx.MX_LAYOUT_FRAGMENT, y, N)
+    torch.cuda.synchronize()
+    qa, ea = orc.quantize(x, block, wx, block_rows=2)
+    qb, eb = orc.quantize(wt, block, ww, block_rows=2)
+    y_ref, mag = orc.gemm(qa, orc.row_exps(ea, 2), wx, qb, orc.row_exps(eb, 2), ww, block, want_mag=True)
+    check_product(host(y), y_ref, mag, "two-row linear M %d block %d" % (M, block))
+    assert not np.array_equal(orc.row_exps(ea, 2), orc.quantize(x, block, wx)[1])     # the shape matters here
 
 
 @pytest.mark.parametrize("M,K,block", [(3, 300 * 64, 16), (8, 270 * 128, 32), (1, 64, 16), (2, 5 * 256, 64)])
