@@ -61,8 +61,7 @@ typedef struct {
                           With 2, rows must be even and the canonical exponent array is
                           [rows/2][cols/block]; the packed layouts repeat the byte for both rows, so
                           mx_gemm does not care (along axis 0 the rows are those of the transposed
-                          matrix: two columns of x).  Not supported (MX_ERR_UNSUPPORTED): mx_cast
-                          unless cols is a multiple of 32. */
+                          matrix: two columns of x). */
 } mx_format;
 
 enum { MX_RNE = 0,  /* round to nearest, ties to the even mantissa */

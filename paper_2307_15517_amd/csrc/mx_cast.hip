@@ -268,6 +268,75 @@ __global__ __launch_bounds__(256) void cast_rows2_kernel(CastArgs a) {
     }
 }
 
+// Two-row blocks whose rows are not whole runs of 32 elements (cols a multiple of the block only): one
+// thread per block, widths and block size as run-time values.  A block of one row is a whole number of
+// bytes (8 | block), so eight elements at a time travel as ws (wd) bytes through a 64-bit word and no two
+// threads write the same byte.  Not a fast path: the shapes of the workloads never come here.
+struct CastAnyArgs {
+    CastArgs c;
+    int64_t pairs, cols;
+    int32_t ws, wd, block, rnd;
+};
+
+__global__ __launch_bounds__(256) void cast_rows2_any_kernel(CastAnyArgs a) {
+    const int64_t nb = a.cols / a.block;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.pairs * nb) return;
+    const int64_t pr = t / nb, j = t - pr * nb;
+    const int ws = a.ws, wd = a.wd, octets = a.block / 8;
+    const int qmax = (1 << (wd - 1)) - 1;
+    auto octet = [&](const uint8_t* base, int64_t first_elem, int w) {      // 8 elements = w bytes
+        uint64_t bits = 0;
+        const uint8_t* p = base + first_elem * w / 8;
+        for (int k = 0; k < w; ++k) bits |= (uint64_t)p[k] << (8 * k);
+        return bits;
+    };
+    int mx = 0;
+    for (int r = 0; r < 2; ++r)
+        for (int o = 0; o < octets; ++o) {
+            const uint64_t bits = octet(a.c.mant, ((2 * pr + r) * a.cols + j * a.block) + 8 * o, ws);
+            for (int i = 0; i < 8; ++i) {
+                const int v = (int)((int64_t)(bits << (64 - ws * (i + 1))) >> (64 - ws));
+                const int m = v < 0 ? -v : v;
+                mx = m > mx ? m : mx;
+            }
+        }
+    int ebyte = 0, sh = 0;
+    if (mx != 0) {
+        const int E = (int)a.c.exps[pr * nb + j] - a.c.bias_s;
+        int E2 = E - (ws - 2) + (31 - __builtin_clz((unsigned)mx));
+        E2 = E2 < a.c.emin_d ? a.c.emin_d : E2;
+        E2 = E2 > a.c.emax_d ? a.c.emax_d : E2;
+        sh = (E - (ws - 2)) - (E2 - (wd - 2));
+        sh = sh > 16 ? 16 : (sh < -16 ? -16 : sh);
+        ebyte = E2 + a.c.bias_d;
+    }
+    for (int r = 0; r < 2; ++r)
+        for (int o = 0; o < octets; ++o) {
+            const int64_t first = ((2 * pr + r) * a.cols + j * a.block) + 8 * o;
+            const uint64_t bits = octet(a.c.mant, first, ws);
+            uint64_t out = 0;
+            for (int i = 0; i < 8; ++i) {
+                const int v = (int)((int64_t)(bits << (64 - ws * (i + 1))) >> (64 - ws));
+                int res = 0;
+                if (mx != 0) {
+                    if (sh >= 0) {
+                        res = v << sh;
+                    } else {
+                        const int k = -sh;
+                        if (a.rnd == MX_RNE) res = (v + ((1 << (k - 1)) - 1) + ((v >> k) & 1)) >> k;
+                        else res = (v + ((v >> 31) & ((1 << k) - 1))) >> k;
+                    }
+                    res = res > qmax ? qmax : (res < -qmax ? -qmax : res);
+                }
+                out |= (uint64_t)((uint32_t)res & ((1u << wd) - 1u)) << (wd * i);
+            }
+            uint8_t* p = a.c.mant_out + first * wd / 8;
+            for (int k = 0; k < wd; ++k) p[k] = (uint8_t)(out >> (8 * k));
+        }
+    a.c.exps_out[pr * nb + j] = (uint8_t)ebyte;
+}
+
 template <int WS, int WD, int B>
 mx_status launch_cast(const CastArgs& a, int rnd, hipStream_t st) {
     if (a.runs_per_row > 0) {
@@ -324,7 +393,6 @@ extern "C" mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t b
     if (batch < 0 || rows < 0 || cols < 0 || cols % fs.block != 0) return MX_ERR_BAD_ARG;
     if (fs.block_rows != fd.block_rows) return MX_ERR_BAD_ARG;
     if (fs.block_rows == 2 && rows % 2 != 0) return MX_ERR_BAD_ARG;
-    if (fs.block_rows == 2 && cols % 32 != 0) return MX_ERR_UNSUPPORTED;     // two-row blocks: whole 32-element runs per row
     if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
     if (!mant || !exps || !mant_out || !exps_out) return MX_ERR_BAD_ARG;
     if (((uintptr_t)mant & 3) || ((uintptr_t)mant_out & 3)) return MX_ERR_BAD_ARG;
@@ -339,6 +407,16 @@ extern "C" mx_status mx_cast(const uint8_t* mant, const uint8_t* exps, int64_t b
     a.emin_d = -a.bias_d;
     a.emax_d = ((1 << fd.exp_bits) - 1) - a.bias_d;
     hipStream_t st = (hipStream_t)stream;
+    if (fs.block_rows == 2 && cols % 32 != 0) {                              // rows are not whole 32-element runs
+        CastAnyArgs g;
+        g.c = a; g.pairs = batch * rows / 2; g.cols = cols;
+        g.ws = fs.mant_bits; g.wd = fd.mant_bits; g.block = fs.block; g.rnd = fd.rounding;
+        const int64_t wgs = ceil_div(g.pairs * (cols / fs.block), 256);
+        if (wgs > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(cast_rows2_any_kernel, dim3((unsigned)wgs), dim3(256), 0, st, g);
+        MX_HIP_LAUNCH_CHECK();
+        return MX_OK;
+    }
     switch (fs.mant_bits) {
         case 2: return dispatch_wd<2>(a, fd.mant_bits, fs.block, fd.rounding, st);
         case 3: return dispatch_wd<3>(a, fd.mant_bits, fs.block, fd.rounding, st);

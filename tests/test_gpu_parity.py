@@ -253,7 +253,6 @@ def test_two_row_blocks_rejections():
     out = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
     assert mx.mx_quantize(xf, 1, 7, 64, 64, 0, 1, f2, buf, out, check=False) == mx.MX_ERR_BAD_ARG          # odd rows
     assert mx.mx_quantize(xf, 1, 32, 15, 16, 0, 0, f2, buf, out, check=False) == mx.MX_ERR_BAD_ARG         # along the rows: odd columns
-    assert mx.mx_cast(buf, buf, 1, 8, 48, f2, mx.fmt(16, 4, block_rows=2), out, out, check=False) == mx.MX_ERR_UNSUPPORTED   # cols % 32
     assert mx.mx_cast(buf, buf, 1, 8, 64, f2, mx.fmt(16, 4), out, out, check=False) == mx.MX_ERR_BAD_ARG                     # block_rows differ
     assert mx.mx_quantize(xf, 1, 8, 64, 64, 0, 1, mx.fmt(16, 8, block_rows=3), buf, out, check=False) == mx.MX_ERR_BAD_ARG
     y = torch.zeros((2, 64), dtype=torch.float32, device=DEV)
@@ -322,6 +321,21 @@ def test_cast_two_row_blocks(block):
         q[:, 6:8] = 0
         ex = rng.integers(0, 256, size=(2, rows // 2, cols // block)).astype(np.uint8)
         check_cast(q, ex, block, ws, wd, rounding=mx.MX_RTZ if ws == 6 else mx.MX_RNE, batch=2, block_rows=2)
+
+
+@pytest.mark.parametrize("block,cols", [(8, 40), (16, 48), (16, 16), (8, 8), (16, 5 * 16)])
+def test_cast_two_row_blocks_any_column_count(block, cols):
+    """Two-row blocks whose rows are not whole runs of 32 elements: all 49 width pairs, both roundings."""
+    rng = np.random.default_rng(970 + cols)
+    rows = 2 * 7
+    for ws in range(2, 9):
+        q = rng.integers(-(2 ** (ws - 1)), 2 ** (ws - 1), size=(2, rows, cols)).astype(np.int8)
+        q[:, ::4] //= 8
+        q[:, 6:8] = 0
+        ex = rng.integers(0, 256, size=(2, rows // 2, cols // block)).astype(np.uint8)
+        for wd in range(2, 9):
+            check_cast(q, ex, block, ws, wd, rounding=mx.MX_RTZ if (ws + wd) % 3 == 0 else mx.MX_RNE, batch=2, block_rows=2)
+    check_cast(q, ex, block, 8, 4, es=8, ed=4, batch=2, block_rows=2)        # exponent clamped both ways
 
 
 def test_cast_rejects_bad_arguments():
