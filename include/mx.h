@@ -269,7 +269,8 @@ MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const
  * Vt_packed: [batch][D x Sk] in fv: V quantized in blocks along the keys (mx_quantize with axis 0)
  *   and packed as a D x Sk matrix, i.e. the right operand mx_gemm would take for P V.
  * All three come from mx_pack / mx_quantize_pack (device, 256-byte aligned, padding as written there).
- * fp: format of P^ (fp.block == fv.block, fp.exp_bits == fv.exp_bits); P^ is never stored.
+ * fp: format of P^ (fp.exp_bits == fv.exp_bits; fp.block is fv.block or a multiple of it); P^ is never
+ *   stored.
  * O: device fp32, element (b, i, d) at O[b*o_batch_stride + i*ldo + d], ldo >= D.
  * Sk >= 1, Sk a multiple of fp.block, D a multiple of fq.block; scale finite.
  * Numerics: S and O accumulate in fp32 like mx_gemm.  P is computed in fp32 with the hardware's
@@ -281,8 +282,10 @@ MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const
  * the packed operands carry their exponents inside the elements, so fq, fk, fv only need sizes that
  * hold whole pairs (Sq for Q, Sk for K, D for V^T); with fp.block_rows = 2 (Sq even) queries 2t and
  * 2t+1 share the exponent of each block of 16 probabilities.
- * Built for MX_LAYOUT_MATRIX with blocks of 16 in all four formats and D <= 128; anything else is
- * MX_ERR_UNSUPPORTED.
+ * Built for the form MX_LAYOUT_MATRIX takes with blocks of 16 (fq, fk, fv declare block 16), D <= 128,
+ * and fp.block 16 or 32; anything else is MX_ERR_UNSUPPORTED.  That form carries the exponent inside
+ * every element, so a tensor quantized with blocks of 32 or 64 enters it as the block-16 tensor of the
+ * same values: mx_pack with block 16 and each exponent byte repeated for the runs of 16 it covers.
  */
 MX_API mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t D, const void* Q_packed, mx_format fq,
                        const void* K_packed, mx_format fk, const void* Vt_packed, mx_format fv, mx_format fp,

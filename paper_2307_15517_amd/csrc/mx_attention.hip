@@ -50,6 +50,7 @@ struct AttnArgs {
     int32_t wp, bias_p, emax_p;
     int32_t vec;                   // O rows may be stored as float4
     float pair;                    // 0 when two neighbouring queries share the exponents of P, else -inf
+    float wide;                    // 0 when P is quantized in blocks of 32 keys (a whole key tile), else -inf
 };
 
 // 16 bytes per lane from global memory straight into LDS: lane L's bytes land at lds_addr + 16*L.
@@ -272,6 +273,7 @@ __global__ __launch_bounds__(256, RQ == 1 ? 2 : 1) void attention_bf16_kernel(At
                 v4i pf[RQ][2];
                 auto unit = [&](int q, int u) {
                     if (u == 0) {
+                        float mb[2];
 #pragma unroll
                         for (int b = 0; b < 2; ++b) {
                             float sm = -__builtin_inff();
@@ -285,6 +287,12 @@ __global__ __launch_bounds__(256, RQ == 1 ? 2 : 1) void attention_bf16_kernel(At
                             // of the two log-probabilities; one-row blocks add -inf to the neighbour's and keep their own
                             m = __builtin_fmaxf(m, g.pair + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
                                                                 0, __builtin_bit_cast(int, m), 0xB1, 0xF, 0xF, true)));
+                            mb[b] = m;
+                        }
+#pragma unroll
+                        for (int b = 0; b < 2; ++b) {
+                            // blocks of 32: the tile's two runs of 16 keys are one block (the same trick: + 0 or + -inf)
+                            float m = __builtin_fmaxf(mb[b], g.wide + mb[b ^ 1]);
                             m = __builtin_fmaxf(m, -200.f);                   // also for all keys masked, or c = 0 with them
                             int E = (int)__builtin_floorf(m);
                             E = E < -g.bias_p ? -g.bias_p : E;
@@ -448,7 +456,7 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
                                   void* stream) {
     if (!format_ok_quant(fq) || !format_ok_quant(fk) || !format_ok_quant(fv) || !format_ok_quant(fp))
         return MX_ERR_BAD_ARG;
-    if (fq.block != fk.block || fq.exp_bits != fk.exp_bits || fp.block != fv.block || fp.exp_bits != fv.exp_bits)
+    if (fq.block != fk.block || fq.exp_bits != fk.exp_bits || fp.block % fv.block != 0 || fp.exp_bits != fv.exp_bits)
         return MX_ERR_BAD_ARG;
     if (layout != MX_LAYOUT_FRAGMENT && layout != MX_LAYOUT_MATRIX) return MX_ERR_BAD_ARG;
     if (batch < 0 || Sq < 0 || Sk < 1 || D < 1 || D % fq.block != 0 || Sk % fp.block != 0 || ldo < D) return MX_ERR_BAD_ARG;
@@ -457,12 +465,13 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
     if (((fq.block_rows == 2 || fp.block_rows == 2) && Sq % 2 != 0) || (fk.block_rows == 2 && Sk % 2 != 0) ||
         (fv.block_rows == 2 && D % 2 != 0))
         return MX_ERR_BAD_ARG;
-    // built for the bfloat16 form of the matrix layout: blocks of 16 in all four formats.  The packed operands carry
-    // their exponents inside the elements, so their block shape (one or two rows) makes no difference here; P's does.
+    // built for the bfloat16 form of the matrix layout, which is declared with blocks of 16.  The packed operands carry
+    // their exponents inside the elements, so their block shape (one or two rows) makes no difference here; P's does:
+    // its blocks are 16 keys, or 32 (one key tile of the kernel).
     if (layout != MX_LAYOUT_MATRIX || !matrix_format_ok(fq) || !matrix_format_ok(fk) || !matrix_format_ok(fv) ||
         !matrix_format_ok(fp))
         return MX_ERR_UNSUPPORTED;
-    if (fq.block != 16 || fp.block != 16 || D > 128) return MX_ERR_UNSUPPORTED;
+    if (fq.block != 16 || fv.block != 16 || (fp.block != 16 && fp.block != 32) || D > 128) return MX_ERR_UNSUPPORTED;
     if (batch == 0 || Sq == 0) return MX_OK;
     if (!Q_packed || !K_packed || !Vt_packed || !O) return MX_ERR_BAD_ARG;
     if (((uintptr_t)Q_packed & 255) || ((uintptr_t)K_packed & 255) || ((uintptr_t)Vt_packed & 255)) return MX_ERR_BAD_ARG;
@@ -479,6 +488,7 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
     g.emax_p = ((1 << fp.exp_bits) - 1) - g.bias_p;
     g.vec = (((uintptr_t)O & 15) == 0 && ldo % 4 == 0 && o_batch_stride % 4 == 0) ? 1 : 0;
     g.pair = fp.block_rows == 2 ? 0.f : -__builtin_inff();
+    g.wide = fp.block == 32 ? 0.f : -__builtin_inff();
     const int dt = (int)ceil_div(D, 32);
     hipStream_t st = (hipStream_t)stream;
     if (gq.ksteps == 2)

@@ -1127,6 +1127,50 @@ def test_attention_fused_two_row_blocks(Sq, Sk, dim, widths):
     assert not np.array_equal(i1["pe"], i2["pe"])
 
 
+@pytest.mark.parametrize("Sq,Sk,dim,widths,rounding", [(70, 288, 64, (8, 8, 6, 5), mx.MX_RNE), (33, 64, 128, (7, 6, 5, 3), mx.MX_RTZ),
+                                                        (130, 2080, 32, (8, 4, 8, 8), mx.MX_RNE)])
+def test_attention_fused_blocks_of_32(Sq, Sk, dim, widths, rounding):
+    """All four tensors quantized in blocks of 32 (the block size of the paper's MXInt8 comparisons).  The
+    packed operands enter as the block-16 tensors of the same values (each exponent byte repeated for its two
+    runs of 16); the probabilities are quantized in blocks of 32 keys inside the kernel."""
+    wq, wk, wp, wv = widths
+    rng = np.random.default_rng(Sq + Sk + 1)
+    H = 2
+    Q = rng.standard_normal((H, Sq, dim)).astype(np.float32)
+    K = (rng.standard_normal((H, Sk, dim)) * rng.choice([0.3, 1.0, 3.0], size=(H, 1, dim))).astype(np.float32)
+    V = (rng.standard_normal((H, Sk, dim)) * rng.choice([0.01, 1.0, 30.0], size=(H, Sk, 1))).astype(np.float32)
+    scale = dim ** -0.5
+
+    def operand(x, w):                                   # x [H, rows, cols], blocks of 32 along cols
+        rows, cols = x.shape[1:]
+        mant, exps = [], []
+        for hd in range(H):
+            q, ex = orc.quantize(x[hd], 32, w, 8, rounding)
+            mant.append(orc.pack_bits(q, w).reshape(-1))
+            exps.append(np.repeat(ex, 2, axis=1).reshape(-1))
+        f16 = mx.fmt(16, w, 8, rounding)
+        return mx.pack(dev(np.concatenate(mant)), dev(np.concatenate(exps)), H, rows, cols, f16, MAT), f16
+
+    A, fq = operand(Q, wq)
+    B, fk = operand(K, wk)
+    Bv, fv = operand(np.ascontiguousarray(V.transpose(0, 2, 1)), wv)
+    fp_ = mx.fmt(32, wp, 8, rounding)
+    O = torch.empty((H, Sq, dim), dtype=torch.float32, device=DEV)
+    mx.mx_attention(H, Sq, Sk, dim, A, fq, B, fk, Bv, fv, fp_, scale, MAT, O, dim, Sq * dim)
+    torch.cuda.synchronize()
+    for hd in range(H):
+        o_ref, info = orc.attention(Q[hd], K[hd], V[hd], 32, wq, wk, wp, wv, scale, 8, rounding)
+        bound, maybe = attention_bound(info, wp, wv, scale, rounding, 8, block=32)
+        assert maybe < 1e-2
+        ratio = np.abs(host(O)[hd].astype(np.float64) - o_ref) / bound
+        assert np.all(ratio <= 1.0), "head %d: worst error %.3g of its bound" % (hd, ratio.max())
+        assert np.median(bound) < 1e-3 * np.abs(o_ref).max()
+    # blocks of 16 give other exponents for the probabilities: the block size matters at these inputs
+    _, i16 = orc.attention(Q[0], K[0], V[0], 16, wq, wk, wp, wv, scale, 8, rounding)
+    _, i32 = orc.attention(Q[0], K[0], V[0], 32, wq, wk, wp, wv, scale, 8, rounding)
+    assert not np.array_equal(np.repeat(i32["pe"], 2, axis=1), i16["pe"])
+
+
 def test_attention_fused_full_size_sampled_heads_and_rows():
     """32 heads x 2048 x 2048 x 128, widths of seed 0, in the launch the benchmark times; the oracle takes two
     heads and a window of query rows each."""
@@ -1151,6 +1195,10 @@ def test_attention_rejections():
     assert call(scale=float("nan")) == mx.MX_ERR_BAD_ARG
     assert call(fk=mx.fmt(32, 8)) == mx.MX_ERR_BAD_ARG      # Q and K must share the block size
     assert call(fq=mx.fmt(32, 4), fk=mx.fmt(32, 4), D=128) == mx.MX_ERR_UNSUPPORTED
+    assert call(fp_=mx.fmt(32, 8)) == mx.MX_OK              # probabilities in blocks of 32 keys
+    assert call(fp_=mx.fmt(64, 8)) == mx.MX_ERR_UNSUPPORTED
+    assert call(fp_=mx.fmt(32, 8), Sk=48) == mx.MX_ERR_BAD_ARG
+    assert call(fv=mx.fmt(32, 8)) == mx.MX_ERR_BAD_ARG     # P's block must be a multiple of V's
     assert call(layout=mx.MX_LAYOUT_FRAGMENT) == mx.MX_ERR_UNSUPPORTED
     assert call(D=256, ldo=256) == mx.MX_ERR_UNSUPPORTED
     f2 = mx.fmt(16, 8, block_rows=2)
