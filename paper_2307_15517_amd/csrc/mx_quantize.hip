@@ -317,8 +317,9 @@ __global__ __launch_bounds__(256) void quantize_axis0_kernel(QuantAxis0Args a) {
         const int64_t col = c0 + cl, row = r0 + 8 * o;                  // rows is a multiple of B: whole blocks or none
         if (col < a.cols && row < a.rows) {
             store_stream<W>(a.mant + ((b * a.cols + col) * row_octets + row / 8) * W, pack8<W>(q));
-            if ((o & (LPB - 1)) == 0 && (col & (a.brows - 1)) == 0)
-                a.exps[(b * (a.cols / a.brows) + col / a.brows) * nb + row / B] = (uint8_t)(E + a.bias);
+            const int rs = a.brows - 1;                                   // 0 or 1: rows per exponent as a shift
+            if ((o & (LPB - 1)) == 0 && (col & rs) == 0)
+                a.exps[(b * (a.cols >> rs) + (col >> rs)) * nb + row / B] = (uint8_t)(E + a.bias);
         }
     }
 }
