@@ -353,7 +353,19 @@ def main():
             qb, eb = orc.quantize(wt, case.block, case.ww)
             orc.gemm(qa, ea, case.wx, qb, eb, case.ww, case.block)
         dt = time.perf_counter() - t0
-        cpu = {"value": round(total_ops / dt / 1e12, 5), "unit": "TOP/s", "cores": threads,
+        # the same code on one thread, on the first 64 activation rows of the first linear (product only scales
+        # with the rows; the weights are quantized once more)
+        case, x, wt = data[0]
+        orc.set_threads(1)
+        t1 = time.perf_counter()
+        qa, ea = orc.quantize(x[:64], case.block, case.wx)
+        qb, eb = orc.quantize(wt, case.block, case.ww)
+        orc.gemm(qa, ea, case.wx, qb, eb, case.ww, case.block)
+        dt1 = time.perf_counter() - t1
+        orc.set_threads(threads)
+        single = {"value": round(2.0 * 64 * case.N * case.K / dt1 / 1e12, 6), "unit": "TOP/s", "cores": 1,
+                  "seconds": round(dt1, 2), "sample": "64 activation rows of %s" % case.name}
+        cpu = {"value": round(total_ops / dt / 1e12, 5), "unit": "TOP/s", "cores": threads, "single_thread": single,
                "kind": "oracle", "seconds": round(dt, 2),
                "sample": "one step of the workload: for each of %s quantize all %d activation rows and all weights, "
                          "then the product (%.1f GOP in all); C oracle with OpenMP over rows"
