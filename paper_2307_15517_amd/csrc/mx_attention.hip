@@ -421,13 +421,9 @@ mx_status launch_attention(AttnArgs& g, int64_t batch, int rnd, hipStream_t st) 
     static_assert(smem * (RQ == 1 ? 2 : 1) <= 160 * 1024, "LDS budget of one compute unit");
     auto k0 = attention_bf16_kernel<KS, DT, MX_RNE, RQ>;
     auto k1 = attention_bf16_kernel<KS, DT, MX_RTZ, RQ>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)k0, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess ||
-            hipFuncSetAttribute((const void*)k1, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return MX_ERR_DEVICE;
-        configured = true;
-    }
+    static std::atomic<uint64_t> done0{0}, done1{0};
+    if (!allow_dynamic_lds((const void*)k0, smem, done0) || !allow_dynamic_lds((const void*)k1, smem, done1))
+        return MX_ERR_DEVICE;
     g.tiles_q = ceil_div(g.Sq, 128 * RQ);
     g.total = g.tiles_q * batch;
     if (g.total > 0x7fffff00LL) return MX_ERR_UNSUPPORTED;

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "mx.h"
 
 namespace mx {
@@ -21,6 +23,19 @@ inline bool format_ok_gemm(const mx_format& f) {
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Raises a kernel's dynamic-LDS limit above the 64 KB default.  The attribute belongs to the (kernel, device) pair,
+// so it is set once per device; `done` is the caller's per-kernel bit set of devices (a static of the launch
+// function).  Safe from several host threads: at worst two of them set the same value.
+inline bool allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return false;
+    const uint64_t bit = 1ull << dev;
+    if (done.load(std::memory_order_acquire) & bit) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    done.fetch_or(bit, std::memory_order_release);
+    return true;
+}
 
 // ---- fragment layout geometry (host and device) ---------------------------------------------
 // Rows in groups of 32, columns in chunks of 4 blocks.  One (group, chunk) record holds

@@ -309,12 +309,8 @@ mx_status launch_bf16(BfArgs& g, int64_t batch, hipStream_t st) {
     constexpr int smem = S * (2 * TM + 2 * TN) * kBfUnitBytes;
     static_assert(smem * OCC <= 160 * 1024, "LDS budget of one compute unit");
     auto kern = gemm_bf16_kernel<TM, TN, S, OCC, QOUT>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return MX_ERR_DEVICE;
-        configured = true;
-    }
+    static std::atomic<uint64_t> done{0};
+    if (!allow_dynamic_lds((const void*)kern, smem, done)) return MX_ERR_DEVICE;
     const int64_t tiles_m = ceil_div(g.M, 64 * TM), tiles_n = ceil_div(g.N, 64 * TN);
     if (tiles_m * tiles_n > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     g.tiles_m = (int32_t)tiles_m;

@@ -400,12 +400,8 @@ constexpr int kStreamDepth = 5;
 template <int WA, int WB, int B, int MR, int NW>
 mx_status launch_stream(const GemmArgs& g, int64_t batch, size_t smem, hipStream_t st) {
     auto kern = gemv_stream_kernel<WA, WB, B, NW, kStreamDepth, MR>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return MX_ERR_DEVICE;
-        configured = true;
-    }
+    static std::atomic<uint64_t> done{0};
+    if (!allow_dynamic_lds((const void*)kern, 160 * 1024, done)) return MX_ERR_DEVICE;
     dim3 grid((unsigned)g.groupsB, (unsigned)batch);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, g);
     MX_HIP_LAUNCH_CHECK();

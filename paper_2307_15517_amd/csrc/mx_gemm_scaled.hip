@@ -466,12 +466,8 @@ mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
     constexpr int smem = pipe > turn ? pipe : turn;
     static_assert(smem * OCC <= 160 * 1024, "LDS budget of one compute unit");
     auto kern = gemm_scaled_kernel<PA, PB, TM, TN, S, OCC, QO>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-            return MX_ERR_DEVICE;
-        configured = true;
-    }
+    static std::atomic<uint64_t> done{0};
+    if (!allow_dynamic_lds((const void*)kern, smem, done)) return MX_ERR_DEVICE;
     const int64_t tiles_m = ceil_div(g.M, 64 * TM), tiles_n = ceil_div(g.N, 64 * TN);
     if (tiles_m * tiles_n > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
     if (g.ksteps * kUnitBytes > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;       // 32-bit offsets along K

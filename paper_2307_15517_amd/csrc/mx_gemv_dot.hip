@@ -289,12 +289,8 @@ mx_status launch_dot_nw(const DotArgs& a, int64_t batch, hipStream_t st) {
                         (size_t)NW * MP * 32 * 4;
     if (smem > 160 * 1024) return MX_ERR_UNSUPPORTED;
     auto kern = gemv_dot_kernel<WB, B, MP, NW, kDotDepth>;
-    static bool configured = false;
-    if (!configured) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return MX_ERR_DEVICE;
-        configured = true;
-    }
+    static std::atomic<uint64_t> done{0};
+    if (!allow_dynamic_lds((const void*)kern, 160 * 1024, done)) return MX_ERR_DEVICE;
     dim3 grid((unsigned)a.g.groupsB, (unsigned)batch);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, a);
     MX_HIP_LAUNCH_CHECK();
