@@ -1127,12 +1127,14 @@ def test_attention_fused_two_row_blocks(Sq, Sk, dim, widths):
     assert not np.array_equal(i1["pe"], i2["pe"])
 
 
-@pytest.mark.parametrize("Sq,Sk,dim,widths,rounding", [(70, 288, 64, (8, 8, 6, 5), mx.MX_RNE), (33, 64, 128, (7, 6, 5, 3), mx.MX_RTZ),
-                                                        (130, 2080, 32, (8, 4, 8, 8), mx.MX_RNE)])
-def test_attention_fused_blocks_of_32(Sq, Sk, dim, widths, rounding):
+@pytest.mark.parametrize("Sq,Sk,dim,widths,rounding,R", [(70, 288, 64, (8, 8, 6, 5), mx.MX_RNE, 1), (33, 64, 128, (7, 6, 5, 3), mx.MX_RTZ, 1),
+                                                          (130, 2080, 32, (8, 4, 8, 8), mx.MX_RNE, 1),
+                                                          (70, 288, 64, (8, 8, 6, 5), mx.MX_RNE, 2), (34, 64, 96, (7, 6, 4, 3), mx.MX_RTZ, 2)])
+def test_attention_fused_blocks_of_32(Sq, Sk, dim, widths, rounding, R):
     """All four tensors quantized in blocks of 32 (the block size of the paper's MXInt8 comparisons).  The
     packed operands enter as the block-16 tensors of the same values (each exponent byte repeated for its two
-    runs of 16); the probabilities are quantized in blocks of 32 keys inside the kernel."""
+    runs of 16); the probabilities are quantized in blocks of 32 keys inside the kernel.  R = 2: blocks of
+    (32, 2), two rows sharing each exponent, in all four tensors."""
     wq, wk, wp, wv = widths
     rng = np.random.default_rng(Sq + Sk + 1)
     H = 2
@@ -1145,21 +1147,21 @@ def test_attention_fused_blocks_of_32(Sq, Sk, dim, widths, rounding):
         rows, cols = x.shape[1:]
         mant, exps = [], []
         for hd in range(H):
-            q, ex = orc.quantize(x[hd], 32, w, 8, rounding)
+            q, ex = orc.quantize(x[hd], 32, w, 8, rounding, block_rows=R)
             mant.append(orc.pack_bits(q, w).reshape(-1))
-            exps.append(np.repeat(ex, 2, axis=1).reshape(-1))
+            exps.append(np.repeat(orc.row_exps(ex, R), 2, axis=1).reshape(-1))
         f16 = mx.fmt(16, w, 8, rounding)
         return mx.pack(dev(np.concatenate(mant)), dev(np.concatenate(exps)), H, rows, cols, f16, MAT), f16
 
     A, fq = operand(Q, wq)
     B, fk = operand(K, wk)
     Bv, fv = operand(np.ascontiguousarray(V.transpose(0, 2, 1)), wv)
-    fp_ = mx.fmt(32, wp, 8, rounding)
+    fp_ = mx.fmt(32, wp, 8, rounding, block_rows=R)
     O = torch.empty((H, Sq, dim), dtype=torch.float32, device=DEV)
     mx.mx_attention(H, Sq, Sk, dim, A, fq, B, fk, Bv, fv, fp_, scale, MAT, O, dim, Sq * dim)
     torch.cuda.synchronize()
     for hd in range(H):
-        o_ref, info = orc.attention(Q[hd], K[hd], V[hd], 32, wq, wk, wp, wv, scale, 8, rounding)
+        o_ref, info = orc.attention(Q[hd], K[hd], V[hd], 32, wq, wk, wp, wv, scale, 8, rounding, block_rows=R)
         bound, maybe = attention_bound(info, wp, wv, scale, rounding, 8, block=32)
         assert maybe < 1e-2
         ratio = np.abs(host(O)[hd].astype(np.float64) - o_ref) / bound
