@@ -5,9 +5,10 @@
 // to four rows the 32x32 MFMA would spend three quarters of its work, and all of its epilogue,
 // on rows that do not exist, and the kernel is bound by instruction issue, not by the matrix
 // cores.  Lane 32*h + i owns output column 32*gb + i and half h of every block (that is what the
-// fragment layout gives it); it adds scale * half-dot into its own fp32 partial sums, and the two
-// halves of a column meet in one cross-lane add at the end.  The activations are unpacked to int8
-// once per workgroup into LDS and read back as broadcasts.
+// fragment layout gives it); the two half dots of a block are added as integers across the wave
+// halves, so that the block's dot is exact before its scale is applied; half h then accumulates
+// every second block in fp32 and the halves meet in one cross-lane add at the end.  The
+// activations are unpacked to int8 once per workgroup into LDS and read back as broadcasts.
 #include "mx_gemm.h"
 
 namespace mx {
@@ -246,16 +247,32 @@ __global__ __launch_bounds__(NW * 64) void gemv_dot_kernel(DotArgs a) {
                 uint32_t exm[MP];
 #pragma unroll
                 for (int m = 0; m < MP; ++m) exm[m] = xe[m * chunks + c];
+                // A block's dot must be exact before it is scaled: its two half dots (this lane's and the
+                // other wave half's) are added as integers -- in fp32, halves that cancel would leave their
+                // rounding behind, next to much smaller blocks.  One swap of the wave halves between the
+                // registers of blocks 2*jp and 2*jp + 1 puts both half dots of block 2*jp + h into half h,
+                // which scales and accumulates that block.
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int ebj = (int)((ebv >> (8 * j)) & 0xFFu) + eadj;
+                for (int jp = 0; jp < 2; ++jp) {
+                    const int sh = 16 * jp + 8 * h;               // exponent byte of block 2*jp + h
+                    const int ebj = (int)((ebv >> sh) & 0xFFu) + eadj;
 #pragma unroll
                     for (int m = 0; m < MP; ++m) {
-                        const uint32_t* xv = x8 + (((m * chunks + c) * 4 + j) * 2 + h) * kHalfDw;
-                        int d = 0;
+                        int dh[2];
 #pragma unroll
-                        for (int q = 0; q < kHalfDw; ++q) d = __builtin_amdgcn_sdot4((int)fb[j][q], (int)xv[q], d, false);
-                        const int e = (int)((exm[m] >> (8 * j)) & 0xFFu) + ebj;
+                        for (int jj = 0; jj < 2; ++jj) {
+                            const int j = 2 * jp + jj;
+                            const uint32_t* xv = x8 + (((m * chunks + c) * 4 + j) * 2 + h) * kHalfDw;
+                            dh[jj] = 0;
+#pragma unroll
+                            for (int q = 0; q < kHalfDw; ++q) dh[jj] = __builtin_amdgcn_sdot4((int)fb[j][q], (int)xv[q], dh[jj], false);
+                        }
+                        // first result: lanes 0..31 keep theirs of block 2*jp, lanes 32..63 get the lower half's of
+                        // block 2*jp + 1; second result: lanes 0..31 get the upper half's of block 2*jp, lanes
+                        // 32..63 keep theirs of block 2*jp + 1
+                        const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)dh[0], (unsigned)dh[1], false, false);
+                        const int d = (int)(sw[0] + sw[1]);
+                        const int e = (int)((exm[m] >> sh) & 0xFFu) + ebj;
                         acc[m] += __builtin_ldexpf((float)d, e);
                     }
                 }

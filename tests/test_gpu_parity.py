@@ -587,6 +587,33 @@ def test_gemm_special_structures():
     assert np.array_equal(host(out)[:, :K], host(y)[0])
 
 
+@pytest.mark.parametrize("M", [1, 2, 4])
+@pytest.mark.parametrize("block", [16, 32, 64])
+def test_gemv_block_halves_that_cancel(M, block):
+    """A block with a large exponent whose two half-block dots cancel exactly, next to blocks 2^20 times
+    smaller that carry the result: the block dot has to be an exact integer before it is scaled (the decode
+    kernels hold the halves of a block in different lanes).  The result must be that of the small blocks."""
+    rng = np.random.default_rng(block + M)
+    K, N, wa, wb = 8 * block, 70, 8, 4
+    qa, ea = random_operand(rng, M, K, block, wa, 100, 104)
+    qb, eb = random_operand(rng, N, K, block, wb, 100, 104)
+    for blk in (0, 5):                                   # the cancelling blocks: a = c everywhere, b = +7 then -7
+        qa[:, blk * block:(blk + 1) * block] = rng.integers(20, 120, size=(M, 1))
+        qb[:, blk * block:blk * block + block // 2] = 7
+        qb[:, blk * block + block // 2:(blk + 1) * block] = -7
+        ea[:, blk] = 120
+        eb[:, blk] = 120
+    A, fa = gpu_operand(qa, ea, block, wa)
+    B, fb = gpu_operand(qb, eb, block, wb)
+    y = mx.gemm(A, fa, B, fb, M, N, K)
+    torch.cuda.synchronize()
+    y_ref, mag = orc.gemm(qa, ea, wa, qb, eb, wb, block, want_mag=True)
+    check_product(host(y)[0], y_ref, mag, "cancelling halves M %d block %d" % (M, block))
+    # the half-block terms are 2^40 times the bound: a kernel that adds them in fp32 cannot pass
+    half = 7.0 * 20 * (block // 2) * 2.0 ** (240 - 254 - (wa - 2) - (wb - 2))
+    assert half > 1e9 * mag.max()
+
+
 def test_gemm_is_deterministic():
     case = inputs.opt125m_layer()[0]
     x, wt = inputs.make(case)

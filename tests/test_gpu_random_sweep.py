@@ -1,0 +1,98 @@
+"""Randomly drawn shapes and formats through the helpers of test_gpu_parity: the same oracle comparisons, on
+cases nobody picked by hand.  Every case is printed before it runs (pytest -s shows it)."""
+import numpy as np
+import pytest
+import torch
+
+import test_gpu_parity as T
+
+pytestmark = pytest.mark.gpu
+mx, orc, say = T.mx, T.orc, T.say
+SEEDS = [1, 2, 3]
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_quantizer(seed):
+    """Both axes, one- and two-row blocks, all block sizes, widths, exponent widths and rounding modes, ragged shapes,
+    zeros sprinkled in: bit-exact."""
+    rng = np.random.default_rng(1000 * seed + 0)
+    for it in range(120):
+        block = int(rng.choice([8, 16, 32, 64])); w = int(rng.integers(2, 9)); e = int(rng.choice([8, 8, 8, 5, 3]))
+        rounding = int(rng.integers(0, 2)); axis = int(rng.integers(0, 2)); R = int(rng.choice([1, 1, 2]))
+        nb = int(rng.integers(1, 40))
+        if axis == 1:
+            rows, cols = int(rng.integers(1, 300)), nb * block
+            if R == 2: rows += rows % 2
+        else:
+            rows, cols = nb * block, int(rng.integers(1, 200))
+            if R == 2: cols += cols % 2
+        say("quantize", it, dict(block=block, w=w, e=e, rounding=rounding, axis=axis, R=R, rows=rows, cols=cols))
+        x = (rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-20, 20, size=(rows, 1)))).astype(np.float32)
+        x[rng.random((rows, cols)) < 0.05] = 0.0
+        f = mx.fmt(block, w, e, rounding, R)
+        mant, exps = mx.quantize(T.dev(x), f, axis=axis)
+        torch.cuda.synchronize()
+        xo = x if axis == 1 else np.ascontiguousarray(x.T)
+        q, ex = orc.quantize(xo, block, w, e, rounding, block_rows=R)
+        assert np.array_equal(T.host(exps), ex.reshape(-1)) and np.array_equal(T.host(mant), orc.pack_bits(q, w).reshape(-1))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_products(seed):
+    """Both layouts, all block sizes and width pairs, decode and tiled row counts, ragged N and K, batches."""
+    rng = np.random.default_rng(1000 * seed + 1)
+    for it in range(60):
+        layout = int(rng.integers(0, 2)); block = int(rng.choice([16, 32, 64])); wa = int(rng.integers(2, 9)); wb = int(rng.integers(2, 9))
+        M = int(rng.choice([1, 2, 3, 5, 8, 9, 31, 33, 100, 129, 257])); N = int(rng.integers(1, 600)); K = int(rng.integers(1, 30)) * block
+        batch = int(rng.choice([1, 1, 2]))
+        say("gemm", it, dict(layout=layout, block=block, wa=wa, wb=wb, M=M, N=N, K=K, batch=batch))
+        ops_a = [T.random_operand(rng, M, K, block, wa, 118, 130) for _ in range(batch)]
+        ops_b = [T.random_operand(rng, N, K, block, wb, 110, 125) for _ in range(batch)]
+        qa = np.stack([o[0] for o in ops_a]); ea = np.stack([o[1] for o in ops_a])
+        qb = np.stack([o[0] for o in ops_b]); eb = np.stack([o[1] for o in ops_b])
+        A, fa = T.gpu_operand(qa, ea, block, wa, batch, layout)
+        B, fb = T.gpu_operand(qb, eb, block, wb, batch, layout)
+        y = mx.gemm(A, fa, B, fb, M, N, K, batch=batch, layout=layout)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            y_ref, mag = orc.gemm(qa[b], ea[b], wa, qb[b], eb[b], wb, block, want_mag=True)
+            me = T.product_magnitude(qa[b], ea[b], wa, qb[b], eb[b], wb, block) if layout == 1 else None
+            T.check_product(T.host(y)[b], y_ref, mag, "random product", me)
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_decode_linear(seed):
+    """mx_linear over row counts 1..8, formats, ragged K and N, aligned and unaligned rows."""
+    rng = np.random.default_rng(1000 * seed + 2)
+    for it in range(30):
+        block = int(rng.choice([16, 32, 64])); wx = int(rng.integers(2, 9)); ww = int(rng.integers(2, 9)); M = int(rng.integers(1, 9))
+        K = int(rng.integers(1, 60)) * block; N = int(rng.integers(1, 300)); off = int(rng.integers(0, 2))
+        say("linear", it, dict(block=block, wx=wx, ww=ww, M=M, K=K, N=N, off=off))
+        xp = (rng.standard_normal((M, K + 4)) * np.exp2(rng.integers(-6, 7, size=(M, 1)))).astype(np.float32)
+        wt = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+        fa, fb = mx.fmt(block, wx), mx.fmt(block, ww)
+        B = mx.quantize_pack(T.dev(wt), fb, mx.MX_LAYOUT_FRAGMENT)
+        scratch = torch.zeros(mx.mx_packed_bytes(1, M, K, fa), dtype=torch.uint8, device=T.DEV)
+        y = torch.full((M, N), 3.0, dtype=torch.float32, device=T.DEV)
+        xv = T.dev(xp)[:, off:off + K]
+        mx.mx_linear(xv, M, K, K + 4, fa, scratch, B, N, fb, mx.MX_LAYOUT_FRAGMENT, y, N)
+        torch.cuda.synchronize()
+        y_ref, mag = orc.linear(xp[:, off:off + K], wt, block, wx, ww, want_mag=True)
+        T.check_product(T.host(y), y_ref, mag, "random linear")
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_attention(seed):
+    """mx_attention over sequence lengths, head dimensions, width draws, one- and two-row blocks."""
+    rng = np.random.default_rng(1000 * seed + 3)
+    for it in range(16):
+        Sq = int(rng.integers(1, 200)); Sk = int(rng.integers(1, 20)) * 16; dim = int(rng.choice([16, 32, 48, 64, 96, 128]))
+        widths = tuple(int(v) for v in rng.integers(2, 9, size=4)); R = int(rng.choice([1, 2]))
+        if R == 2: Sq += Sq % 2
+        say("attention", it, dict(Sq=Sq, Sk=Sk, dim=dim, widths=widths, R=R))
+        Q = rng.standard_normal((2, Sq, dim)).astype(np.float32)
+        K = rng.standard_normal((2, Sk, dim)).astype(np.float32)
+        V = rng.standard_normal((2, Sk, dim)).astype(np.float32)
+        r = T.run_attention(Q, K, V, widths, 0.9 * dim ** -0.5, block_rows=R, max_maybe=5e-2)
+        say("   worst/bound", r)
+
