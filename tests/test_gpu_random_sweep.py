@@ -96,3 +96,82 @@ def test_random_attention(seed):
         r = T.run_attention(Q, K, V, widths, 0.9 * dim ** -0.5, block_rows=R, max_maybe=5e-2)
         say("   worst/bound", r)
 
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_wide_exponents_fragment_layout(seed):
+    """Fragment layout, block exponents over 60 binades, every row class (dot, stream, tiled kernels), with a block
+    whose halves cancel sprinkled in: the plain criterion holds on any data there."""
+    rng = np.random.default_rng(7000 + 10 * seed + 0)
+    for it in range(60):
+        block = int(rng.choice([16, 32, 64])); wa = int(rng.integers(2, 9)); wb = int(rng.integers(2, 9))
+        M = int(rng.choice([1, 2, 3, 4, 7, 8, 9, 40, 130])); N = int(rng.integers(1, 300)); K = int(rng.integers(1, 24)) * block
+        say("a", it, dict(block=block, wa=wa, wb=wb, M=M, N=N, K=K))
+        qa, _ = T.random_operand(rng, M, K, block, wa, 0, 1); qb, _ = T.random_operand(rng, N, K, block, wb, 0, 1)
+        base = rng.integers(60, 200, size=(1, K // block))
+        ea = (base + rng.integers(-30, 31, size=(M, K // block))).clip(0, 255).astype(np.uint8)
+        eb = (255 - base + rng.integers(-30, 31, size=(N, K // block))).clip(0, 255).astype(np.uint8)
+        # sprinkle blocks whose halves cancel
+        if K // block >= 2:
+            blk = int(rng.integers(0, K // block))
+            qa[:, blk * block:(blk + 1) * block] = 1
+            qb[:, blk * block:blk * block + block // 2] = 1; qb[:, blk * block + block // 2:(blk + 1) * block] = -1
+        A, fa = T.gpu_operand(qa, ea, block, wa); B, fb = T.gpu_operand(qb, eb, block, wb)
+        y = mx.gemm(A, fa, B, fb, M, N, K); torch.cuda.synchronize()
+        y_ref, mag = orc.gemm(qa, ea, wa, qb, eb, wb, block, want_mag=True)
+        T.check_product(T.host(y)[0], y_ref, mag, "random wide exponents")
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_fused_quantize_pack(seed):
+    """mx_quantize_pack against mx_quantize + mx_pack (same bytes) on both layouts, one- and two-row blocks, batches;
+    mx_unpack returns the oracle's canonical form."""
+    rng = np.random.default_rng(7000 + 10 * seed + 1)
+    for it in range(60):
+        layout = int(rng.integers(0, 2)); block = int(rng.choice([16, 32, 64])); w = int(rng.integers(2, 9)); R = int(rng.choice([1, 1, 2]))
+        rounding = int(rng.integers(0, 2)); batch = int(rng.choice([1, 2, 3])); rows = int(rng.integers(1, 200)); cols = int(rng.integers(1, 20)) * block
+        if R == 2: rows += rows % 2
+        say("b", it, dict(layout=layout, block=block, w=w, R=R, rounding=rounding, batch=batch, rows=rows, cols=cols))
+        x = (rng.standard_normal((batch, rows, cols)) * np.exp2(rng.integers(-20, 20, size=(batch, rows, 1)))).astype(np.float32)
+        x[rng.random(x.shape) < 0.03] = 0.0
+        f = mx.fmt(block, w, 8, rounding, R)
+        xd = T.dev(x)
+        n = mx.mx_packed_bytes(batch, rows, cols, f, layout)
+        p1 = torch.zeros(n, dtype=torch.uint8, device=T.DEV); p2 = torch.zeros(n, dtype=torch.uint8, device=T.DEV)
+        mant, exps = mx.quantize(xd, f)
+        mx.mx_pack(mant, exps, batch, rows, cols, f, layout, p1)
+        mx.mx_quantize_pack(xd, batch, rows, cols, cols, rows * cols, f, layout, p2)
+        um, ue = mx.unpack(p2, batch, rows, cols, f, layout)
+        torch.cuda.synchronize()
+        assert torch.equal(p1, p2)
+        for b in range(batch):
+            q, ex = orc.quantize(x[b], block, w, 8, rounding, block_rows=R)
+            assert np.array_equal(T.host(um).reshape(batch, -1)[b], orc.pack_bits(q, w).reshape(-1))
+            assert np.array_equal(T.host(ue).reshape(batch, -1)[b], ex.reshape(-1))
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_minifloat(seed):
+    """Block Minifloat / Block Logarithm quantizer over every (e, m) with 1 + e + m <= 8, bit-exact."""
+    rng = np.random.default_rng(7000 + 10 * seed + 2)
+    for it in range(60):
+        block = int(rng.choice([8, 16, 32, 64])); e = int(rng.integers(1, 8)); m = int(rng.integers(0, 8 - e)); rounding = int(rng.integers(0, 2))
+        rows = int(rng.integers(1, 100)); cols = int(rng.integers(1, 40)) * block
+        say("c", it, dict(block=block, e=e, m=m, rounding=rounding, rows=rows, cols=cols))
+        x = (rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-30, 30, size=(rows, 1)))).astype(np.float32)
+        x[rng.random(x.shape) < 0.03] = 0.0
+        T.run_minifloat(x, block, e, m, rounding)
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_cast(seed):
+    """Width cast over width pairs, exponent widths, roundings, one- and two-row blocks, any column count."""
+    rng = np.random.default_rng(7000 + 10 * seed + 3)
+    for it in range(60):
+        block = int(rng.choice([8, 16, 32, 64])); ws = int(rng.integers(2, 9)); wd = int(rng.integers(2, 9)); R = int(rng.choice([1, 1, 2]))
+        es = int(rng.choice([8, 8, 5])); ed = int(rng.choice([8, 8, 4])); rounding = int(rng.integers(0, 2)); batch = int(rng.choice([1, 2]))
+        rows = int(rng.integers(1, 60)); cols = int(rng.integers(1, 20)) * block
+        if R == 2: rows += rows % 2
+        say("d", it, dict(block=block, ws=ws, wd=wd, R=R, es=es, ed=ed, rounding=rounding, batch=batch, rows=rows, cols=cols))
+        q = rng.integers(-(2 ** (ws - 1)), 2 ** (ws - 1), size=(batch, rows, cols)).astype(np.int8)
+        q[:, :, ::3] //= 4
+        ex = rng.integers(0, 2 ** es, size=(batch, rows // R, cols // block)).astype(np.uint8)
+        T.check_cast(q, ex, block, ws, wd, es, ed, rounding, batch, R)
