@@ -175,3 +175,79 @@ def test_random_cast(seed):
         q[:, :, ::3] //= 4
         ex = rng.integers(0, 2 ** es, size=(batch, rows // R, cols // block)).astype(np.uint8)
         T.check_cast(q, ex, block, ws, wd, es, ed, rounding, batch, R)
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_fused_linear_layer(seed):
+    """mx_gemm_q against mx_gemm, the bias add and mx_quantize_pack run one by one (same bytes): block sizes, one- and
+    two-row blocks, widths, ragged M, batches, with and without bias."""
+    rng = np.random.default_rng(9000 + 10 * seed + 0)
+    MAT, DEV = T.MAT, T.DEV
+    for it in range(30):
+        block = int(rng.choice([16, 32, 64])); R = int(rng.choice([1, 2])); wx = int(rng.integers(2, 9)); ww = int(rng.integers(2, 5)); wo = int(rng.integers(2, 9))
+        M = int(rng.integers(1, 300)); K = int(rng.integers(1, 12)) * 64; N = int(rng.integers(1, 12)) * 64; batch = int(rng.choice([1, 2]))
+        if R == 2: M += M % 2
+        with_bias = bool(rng.integers(0, 2))
+        say("gemm_q", it, dict(block=block, R=R, wx=wx, ww=ww, wo=wo, M=M, K=K, N=N, batch=batch, bias=with_bias))
+        x = rng.standard_normal((batch, M, K)).astype(np.float32)
+        wt = (rng.standard_normal((batch, N, K)) * 0.02).astype(np.float32)
+        bias = (rng.standard_normal(N) * 0.1).astype(np.float32)
+        fa, fb = mx.fmt(block, wx, block_rows=R), mx.fmt(block, ww, block_rows=R)
+        fbias, fo = mx.fmt(block, 4), mx.fmt(block, wo, block_rows=R)
+        A = mx.quantize_pack(T.dev(x), fa, MAT); B = mx.quantize_pack(T.dev(wt), fb, MAT)
+        bm, be = mx.quantize(T.dev(bias.reshape(1, N)), fbias)
+        n_out = mx.mx_packed_bytes(batch, M, N, fo, MAT)
+        out = torch.zeros(n_out, dtype=torch.uint8, device=DEV)
+        st = mx.mx_gemm_q(batch, M, N, K, A, fa, B, fb, MAT, bm if with_bias else None, be if with_bias else None, fbias, fo, out, check=False)
+        if st == mx.MX_ERR_UNSUPPORTED:
+            say("   unsupported"); continue
+        assert st == mx.MX_OK, st
+        y = mx.gemm(A, fa, B, fb, M, N, K, batch=batch, layout=MAT)
+        if with_bias: y = y + mx.dequantize(bm, be, 1, 1, N, fbias)[0]
+        ref = torch.zeros(n_out, dtype=torch.uint8, device=DEV)
+        mx.mx_quantize_pack(y.contiguous(), batch, M, N, N, M * N, fo, MAT, ref)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_quantize_pack_down_the_columns(seed):
+    """mx_quantize_pack_axis0 against the oracle's quantization of the transposed matrix: ragged shapes, row pitch,
+    one- and two-row blocks, narrow exponents, batches."""
+    rng = np.random.default_rng(9000 + 10 * seed + 1)
+    MAT, DEV = T.MAT, T.DEV
+    for it in range(40):
+        rows = int(rng.integers(1, 40)) * 16; cols = int(rng.integers(1, 200)); w = int(rng.integers(2, 9)); R = int(rng.choice([1, 2])); rounding = int(rng.integers(0, 2))
+        e = int(rng.choice([8, 8, 5])); batch = int(rng.choice([1, 3])); pad = int(rng.choice([0, 1, 4]))
+        if R == 2: cols += cols % 2
+        say("axis0", it, dict(rows=rows, cols=cols, w=w, R=R, rounding=rounding, e=e, batch=batch, pad=pad))
+        x = (rng.standard_normal((batch, rows, cols + pad)) * np.exp2(rng.integers(-10, 10, size=(batch, 1, cols + pad)))).astype(np.float32)
+        f = mx.fmt(16, w, e, rounding, R)
+        xd = T.dev(x); xv = xd[:, :, :cols]
+        got = torch.zeros((mx.mx_packed_bytes(batch, cols, rows, f, MAT),), dtype=torch.uint8, device=DEV)
+        mx.mx_quantize_pack_axis0(xv, batch, rows, cols, cols + pad, rows * (cols + pad), f, MAT, got)
+        um, ue = mx.unpack(got, batch, cols, rows, f, MAT)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            oq, oe = orc.quantize(np.ascontiguousarray(x[b, :, :cols].T), 16, w, e, rounding, block_rows=R)
+            assert np.array_equal(T.host(um).reshape(batch, -1)[b], orc.pack_bits(oq, w).reshape(-1))
+            assert np.array_equal(T.host(ue).reshape(batch, -1)[b], oe.reshape(-1))
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_matrix_layout_products(seed):
+    """Matrix-core layout on heavy-tailed activations and N(0, 0.02) weights (the workloads' structure): all block sizes
+    and width pairs, ragged M, N, K, batches; the plain criterion."""
+    rng = np.random.default_rng(9000 + 10 * seed + 2)
+    MAT, DEV = T.MAT, T.DEV
+    for it in range(40):
+        block = int(rng.choice([16, 32, 64])); wa = int(rng.integers(2, 9)); wb = int(rng.integers(2, 9))
+        M = int(rng.integers(1, 400)); N = int(rng.integers(1, 700)); K = int(rng.integers(1, 20)) * block; batch = int(rng.choice([1, 2]))
+        say("matrix gemm", it, dict(block=block, wa=wa, wb=wb, M=M, N=N, K=K, batch=batch))
+        x = (rng.standard_t(3, size=(batch, M, K))).astype(np.float32)
+        wt = (rng.standard_normal((batch, N, K)) * 0.02).astype(np.float32)
+        fa, fb = mx.fmt(block, wa), mx.fmt(block, wb)
+        A = mx.quantize_pack(T.dev(x), fa, MAT); B = mx.quantize_pack(T.dev(wt), fb, MAT)
+        y = mx.gemm(A, fa, B, fb, M, N, K, batch=batch, layout=MAT); torch.cuda.synchronize()
+        for b in range(batch):
+            y_ref, mag = orc.linear(x[b], wt[b], block, wa, wb, want_mag=True)
+            T.check_product(T.host(y)[b], y_ref, mag, "matrix gemm")
