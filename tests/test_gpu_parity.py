@@ -1121,6 +1121,20 @@ def test_attention_fused_rounding_and_exponent_width_of_p(rounding, e_pv, wp):
     say("worst/bound", run_attention(Q, K, V, (7, 7, wp, 6), 0.5, rounding=rounding, e_pv=e_pv))
 
 
+@pytest.mark.parametrize("scale", [-0.3, 0.0, 1e-3, 2.0])
+def test_attention_fused_scales(scale):
+    """Negative scale (the smallest score gets the largest probability), zero (uniform probabilities whatever the
+    scores), a tiny and a large one; 144 keys: a ragged last tile of 32."""
+    rng = np.random.default_rng(91)
+    Q = rng.standard_normal((2, 70, 64)).astype(np.float32)
+    K = rng.standard_normal((2, 144, 64)).astype(np.float32)
+    V = rng.standard_normal((2, 144, 64)).astype(np.float32)
+    say("scale", scale, "worst/bound", run_attention(Q, K, V, (8, 7, 6, 5), scale, max_maybe=5e-2))
+    if scale == 0.0:                                     # and the probabilities are exactly 1/144 in the oracle
+        _, info = orc.attention(Q[0], K[0], V[0], 16, 8, 7, 6, 5, scale)
+        assert np.all(info["P"] == 1.0 / 144)
+
+
 def test_attention_fused_peaked_and_flat_rows():
     """Rows whose softmax is one-hot (a key matching the query by a wide margin), rows with all scores
     equal, and ordinary rows, in one call: the exact cases of the oracle's pins, through the kernel.  Their
