@@ -251,3 +251,47 @@ def test_random_matrix_layout_products(seed):
         for b in range(batch):
             y_ref, mag = orc.linear(x[b], wt[b], block, wa, wb, want_mag=True)
             T.check_product(T.host(y)[b], y_ref, mag, "matrix gemm")
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_strided_inputs(seed):
+    """Views with a row pitch, a batch pitch and an unaligned first element through mx_quantize (both axes, one- and
+    two-row blocks) and, where the alignment allows, mx_quantize_pack on both layouts."""
+    rng = np.random.default_rng(11000 + seed)
+    DEV = T.DEV
+    for it in range(80):
+        block = int(rng.choice([8, 16, 32, 64])); w = int(rng.integers(2, 9)); R = int(rng.choice([1, 1, 2])); axis = int(rng.integers(0, 2))
+        rounding = int(rng.integers(0, 2)); batch = int(rng.choice([1, 2, 3]))
+        padc = int(rng.choice([0, 1, 3, 4, 8])); padr = int(rng.choice([0, 1, 2])); off = int(rng.choice([0, 0, 1, 2, 4]))
+        nb = int(rng.integers(1, 24))
+        if axis == 1:
+            rows, cols = int(rng.integers(1, 150)), nb * block
+            if R == 2: rows += rows % 2
+        else:
+            rows, cols = nb * block, int(rng.integers(1, 150))
+            if R == 2: cols += cols % 2
+        say("quantize", it, dict(block=block, w=w, R=R, axis=axis, rounding=rounding, batch=batch, rows=rows, cols=cols, padc=padc, padr=padr, off=off))
+        big = (rng.standard_normal((batch, rows + padr, cols + padc + off)) * np.exp2(rng.integers(-12, 12, size=(batch, rows + padr, 1)))).astype(np.float32)
+        bd = T.dev(big)
+        xv = bd[:, :rows, off:off + cols]
+        f = mx.fmt(block, w, 8, rounding, R)
+        mant, exps = mx.quantize(xv, f, axis=axis)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            xo = big[b, :rows, off:off + cols]
+            xo = np.ascontiguousarray(xo if axis == 1 else xo.T)
+            q, ex = orc.quantize(xo, block, w, 8, rounding, block_rows=R)
+            assert np.array_equal(T.host(exps).reshape(batch, -1)[b], ex.reshape(-1)), "exps"
+            assert np.array_equal(T.host(mant).reshape(batch, -1)[b], orc.pack_bits(q, w).reshape(-1)), "mant"
+        # the fused quantize+pack on the same view (blocks of 16/32/64 only; the matrix layout wants 16-byte aligned rows)
+        if axis == 1 and block >= 16:
+            for layout in (0, 1):
+                n = mx.mx_packed_bytes(batch, rows, cols, f, layout)
+                p = torch.zeros(n, dtype=torch.uint8, device=DEV)
+                st = mx.mx_quantize_pack(xv, batch, rows, cols, xv.stride(1), xv.stride(0), f, layout, p, check=False)
+                if st == mx.MX_ERR_UNSUPPORTED:
+                    say("   layout", layout, "unsupported (alignment)"); continue
+                assert st == mx.MX_OK, st
+                um, ue = mx.unpack(p, batch, rows, cols, f, layout)
+                torch.cuda.synchronize()
+                assert torch.equal(um, mant) and torch.equal(ue, exps), ("fused", layout)
