@@ -295,3 +295,37 @@ def test_random_strided_inputs(seed):
                 um, ue = mx.unpack(p, batch, rows, cols, f, layout)
                 torch.cuda.synchronize()
                 assert torch.equal(um, mant) and torch.equal(ue, exps), ("fused", layout)
+
+
+@pytest.mark.parametrize("seed", SEEDS[:2])
+def test_random_dequantize_and_round_trips(seed):
+    """mx_dequantize on arbitrary codes and exponent bytes (exact inside the fp32 range, infinity beyond it), and
+    mx_pack / mx_unpack round trips on arbitrary bytes for both layouts, one- and two-row blocks."""
+    rng = np.random.default_rng(13000 + seed)
+    for it in range(80):
+        block = int(rng.choice([8, 16, 32, 64])); w = int(rng.integers(2, 9)); e = int(rng.choice([8, 8, 6, 3])); R = int(rng.choice([1, 2]))
+        batch = int(rng.choice([1, 2])); rows = int(rng.integers(1, 120)); cols = int(rng.integers(1, 24)) * block
+        if R == 2: rows += rows % 2
+        say("dequantize", it, dict(block=block, w=w, e=e, R=R, batch=batch, rows=rows, cols=cols))
+        q = rng.integers(-(2 ** (w - 1)), 2 ** (w - 1), size=(batch, rows, cols)).astype(np.int8)
+        ex = rng.integers(0, 2 ** e, size=(batch, rows // R, cols // block)).astype(np.uint8)
+        f = mx.fmt(block, w, e, block_rows=R)
+        mant = T.dev(orc.pack_bits(q.reshape(-1, cols), w).reshape(-1))
+        y = T.host(mx.dequantize(mant, T.dev(ex.reshape(-1)), batch, rows, cols, f)).astype(np.float64)
+        for b in range(batch):
+            want = orc.dequantize(q[b], orc.row_exps(ex[b], R), block, w, e)
+            big = np.abs(want) > 3.4028234663852886e38                  # beyond fp32: the device gives infinity
+            ok = (y[b] == want) | (np.abs(want) < 2.0 ** -126) | big    # exact unless below the fp32 normal range
+            assert ok.all(), ("dequantize", np.argwhere(~ok)[:5].tolist())
+            assert np.all((np.abs(y[b] - want) <= 2.0 ** -149) | big)
+            assert np.all(np.isinf(y[b][big]))
+        if block >= 16:
+            for layout in (0, 1):
+                lo, hi = (0, 256)
+                if layout == 1: lo, hi = ((w - 1, 254) if block == 16 else (0, 251))
+                ex2 = rng.integers(lo, hi, size=(batch, rows // R, cols // block)).astype(np.uint8)
+                f8 = mx.fmt(block, w, 8, block_rows=R)
+                p = mx.pack(mant, T.dev(ex2.reshape(-1)), batch, rows, cols, f8, layout)
+                m2, e2 = mx.unpack(p, batch, rows, cols, f8, layout)
+                torch.cuda.synchronize()
+                assert torch.equal(m2, mant) and np.array_equal(T.host(e2), ex2.reshape(-1)), ("roundtrip", layout)
