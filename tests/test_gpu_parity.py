@@ -136,6 +136,34 @@ def test_quantize_workload_shapes():
         check_quantize(wt[:512], case.block, case.ww)
 
 
+def test_quantize_and_dequantize_beyond_32_bit_offsets():
+    """2^31 + 2^21 elements (8.6 GB of fp32 in, 2.1 GB of mantissas out): element and byte offsets that do not fit
+    32 bits.  The input is one seeded tile of 256 rows repeated down the tensor, so every repetition must come out
+    as the tile's own quantization, which is checked against the oracle."""
+    rng = np.random.default_rng(31)
+    cols, tile_rows = 8192, 256
+    reps = 2 ** 31 // (cols * tile_rows) + 1
+    tile = (rng.standard_normal((tile_rows, cols)) * np.exp2(rng.integers(-8, 8, size=(tile_rows, 1)))).astype(np.float32)
+    f = mx.fmt(32, 8)
+    td = dev(tile)
+    m_tile, e_tile = mx.quantize(td, f)
+    q, ex = orc.quantize(tile, 32, 8)
+    assert np.array_equal(host(e_tile), ex.reshape(-1)) and np.array_equal(host(m_tile), orc.pack_bits(q, 8).reshape(-1))
+    xd = td.repeat(reps, 1)
+    assert xd.numel() > 2 ** 31
+    mant, exps = mx.quantize(xd, f)
+    torch.cuda.synchronize()
+    assert bool((mant.view(reps, -1) == m_tile.view(1, -1)).all()), "mantissas of a repetition differ"
+    assert bool((exps.view(reps, -1) == e_tile.view(1, -1)).all()), "exponents of a repetition differ"
+    y = mx.dequantize(mant, exps, 1, reps * tile_rows, cols, f)
+    y_tile = mx.dequantize(m_tile, e_tile, 1, tile_rows, cols, f)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(y_tile)[0].astype(np.float64), orc.dequantize(q, ex, 32, 8))
+    assert bool((y.view(reps, -1) == y_tile.view(1, -1)).all()), "values of a repetition differ"
+    del xd, mant, exps, y
+    torch.cuda.empty_cache()
+
+
 def test_quantize_is_deterministic_and_ignores_stale_output():
     rng = np.random.default_rng(6)
     x = dev(special_values(rng, 64, 1024))
@@ -612,6 +640,62 @@ def test_gemv_block_halves_that_cancel(M, block):
     # the half-block terms are 2^40 times the bound: a kernel that adds them in fp32 cannot pass
     half = 7.0 * 20 * (block // 2) * 2.0 ** (240 - 254 - (wa - 2) - (wb - 2))
     assert half > 1e9 * mag.max()
+
+
+def test_gemm_output_beyond_32_bit_offsets():
+    """32768 x 65600 outputs (2^31 + 2^21 elements, 8.6 GB): output offsets that do not fit 32 bits, through the
+    block-scaled, the bfloat16 and the int8 tiled kernels; the oracle takes windows of rows at both ends."""
+    rng = np.random.default_rng(32)
+    M, N, K = 32768, 65600, 64
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    wt = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    Y = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    assert Y.numel() > 2 ** 31
+    for layout, block in ((MAT, 32), (MAT, 16), (mx.MX_LAYOUT_FRAGMENT, 32)):
+        fa, fb = mx.fmt(block, 8), mx.fmt(block, 4)
+        A = mx.quantize_pack(dev(x), fa, layout)
+        B = mx.quantize_pack(dev(wt), fb, layout)
+        Y.fill_(7.0)
+        mx.mx_gemm(1, M, N, K, A, fa, B, fb, layout, Y, N, M * N)
+        torch.cuda.synchronize()
+        qa, ea = orc.quantize(x, block, 8)
+        qb, eb = orc.quantize(wt, block, 4)
+        for r0, r1 in ((0, 6), (16380, 16390), (M - 6, M)):
+            y_ref, mag = orc.gemm(qa[r0:r1], ea[r0:r1], 8, qb, eb, 4, block, want_mag=True)
+            check_product(host(Y[r0:r1]), y_ref, mag, "layout %d block %d rows %d.." % (layout, block, r0))
+            assert not np.any(host(Y[r0:r1]) == 7.0)
+    del Y
+    torch.cuda.empty_cache()
+
+
+def test_packed_operand_beyond_32_bit_offsets():
+    """A right operand of 196608 x 45056 weights: 35 GB of fp32 into mx_quantize_pack, 6.9 GB (matrix layout) and
+    4.7 GB (fragment layout) packed -- byte offsets beyond 32 bits inside the operand, through the fused quantizer,
+    the prefill kernel, the tiled int8 kernel and the decode kernels.  The weights are one seeded tile of 512 rows
+    repeated, so output column n must equal column n mod 512, and the first 512 columns are checked against the
+    oracle."""
+    rng = np.random.default_rng(33)
+    N, K, T_ = 196608, 45056, 512
+    tile = (rng.standard_normal((T_, K)) * 0.02).astype(np.float32)
+    wd = dev(tile).repeat(N // T_, 1)
+    assert wd.numel() * 0.75 > 2 ** 32
+    qb, eb = orc.quantize(tile, 32, 4)
+    fa, fb = mx.fmt(32, 8), mx.fmt(32, 4)
+    for layout, Ms in ((MAT, (64,)), (mx.MX_LAYOUT_FRAGMENT, (1, 8, 40))):
+        B = mx.quantize_pack(wd, fb, layout)
+        assert B.numel() > 2 ** 32
+        for M in Ms:
+            x = rng.standard_normal((M, K)).astype(np.float32)
+            A = mx.quantize_pack(dev(x), fa, layout)
+            y = mx.gemm(A, fa, B, fb, M, N, K, layout=layout)[0]
+            torch.cuda.synchronize()
+            assert bool((y.view(M, N // T_, T_) == y[:, :T_].reshape(M, 1, T_)).all()), "columns of a repetition differ"
+            qa, ea = orc.quantize(x, 32, 8)
+            y_ref, mag = orc.gemm(qa, ea, 8, qb, eb, 4, 32, want_mag=True)
+            check_product(host(y[:, :T_]), y_ref, mag, "layout %d M %d" % (layout, M))
+        del B
+    del wd
+    torch.cuda.empty_cache()
 
 
 def test_gemm_is_deterministic():
