@@ -102,6 +102,26 @@ __global__ __launch_bounds__(256) void quantize_minifloat_kernel(MiniArgs a) {
                 const bool magic_overflows = L - m + 23 > 127;
                 const float magic = __uint_as_float((uint32_t)((low_ok && !magic_overflows ? L : -126) - m + 23 + 127) << 23);
                 const uint32_t par0 = m == 0 ? (uint32_t)(L & 1) : 0u;         // m = 0: the code's parity is the exponent's
+                // Ordinary data has no element below the format's smallest normal value (2^-cmax of the block
+                // maximum; zeros count as below): when no lane of the wave holds one, only the first rule runs.
+                uint32_t lowest = __float_as_uint(xv[0]) & 0x7fffffffu;
+#pragma unroll
+                for (int i = 1; i < 4; ++i) {
+                    const uint32_t ab = __float_as_uint(xv[i]) & 0x7fffffffu;
+                    lowest = ab < lowest ? ab : lowest;
+                }
+                if (__builtin_amdgcn_ballot_w64(lowest < minnorm) == 0) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t bits = __float_as_uint(xv[i]);
+                        const uint32_t ab = bits & 0x7fffffffu;
+                        uint32_t r = ab;
+                        if (a.rnd == MX_RNE) r += half_m1 + (((ab >> sb) & 1u) ^ par0);
+                        uint32_t code = (r >> sb) - rebase;
+                        code = code > code_max ? code_max : code;
+                        out |= (((bits >> 31) << (e + m)) | code) << (8 * i);
+                    }
+                } else
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const uint32_t bits = __float_as_uint(xv[i]);
