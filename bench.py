@@ -264,7 +264,7 @@ def main():
                 nring = max(2, int(1.3e9 // B0.numel()))
                 Bs = [B0] + [B0.clone() for _ in range(nring - 1)]
                 xd = torch.from_numpy(x).to(dev)
-                scratch = torch.zeros(mx.mx_packed_bytes(1, M, dc.K, fa, LF), dtype=torch.uint8, device=dev)
+                scratch = mx.linear_workspace(M, dc.K, dc.N, fa, fb, dev)
                 y = torch.empty((M, dc.N), dtype=torch.float32, device=dev)
                 calls = [mx.bound("mx_linear", xd, M, dc.K, dc.K, fa, scratch, Bw, dc.N, fb, LF, y, dc.N) for Bw in Bs]
                 ms = time_launches(lambda i: calls[i % nring](), 2 * nring)

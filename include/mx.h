@@ -13,8 +13,10 @@
  * Conventions for every entry point
  *   - Pointers named x, y, Y, mant, exps, packed, A_packed, B_packed are DEVICE
  *     pointers (e.g. a torch tensor's data_ptr()).  The library allocates nothing,
- *     frees nothing, keeps no state between calls, and never synchronizes: all work
- *     is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream).
+ *     frees nothing and never synchronizes: all work is enqueued on `stream` (a
+ *     hipStream_t passed as void*, NULL = default stream).  Between calls it keeps no
+ *     data; the only host state is, per kernel that needs more than 64 KB of LDS, a
+ *     set of the devices on which that limit has been raised (set once, thread-safe).
  *   - The return value is an mx_status.  Nothing throws or aborts across this
  *     boundary.  MX_ERR_BAD_ARG: a null pointer, a negative size, a size that is not
  *     a whole number of blocks, a format outside the ranges stated at mx_format, or
@@ -119,7 +121,8 @@ MX_API size_t mx_exps_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format
  *           mant, exps receive the canonical form of the TRANSPOSED matrices,
  *           batch x cols x rows (the layout the right operand of a product needs
  *           when the reduction runs over the rows of x).
- * x must be 4-byte aligned; row_stride >= cols; mant and exps are written densely.
+ * x must be 4-byte aligned; row_stride >= cols; mant and exps are written densely; mant must be
+ * 16-byte aligned (any allocation's start is).
  */
 MX_API mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
                       int64_t batch_stride, int32_t axis, mx_format f, uint8_t* mant, uint8_t* exps,
@@ -129,7 +132,7 @@ MX_API mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_
  * Inverse of the quantizer's encoding (Section 3.2 "dequantize"): y[b][r][c] =
  * q * 2^(E - (w-2)) as fp32, dense batch x rows x cols, from the canonical form of
  * batch x rows x cols (blocks along the columns).  Exact whenever the value is
- * representable in fp32 (always, except below the fp32 subnormal spacing).
+ * representable in fp32 (always, except below the fp32 subnormal spacing).  y must be 16-byte aligned.
  */
 MX_API mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows,
                         int64_t cols, mx_format f, float* y, void* stream);
@@ -233,7 +236,8 @@ MX_API mx_status mx_unpack(const void* packed, int64_t batch, int64_t rows, int6
  * N x K (one row per output column, like torch.nn.Linear.weight).
  * fa.block == fb.block and fa.exp_bits == fb.exp_bits are required.
  * Y: fp32, element (b, m, n) at Y[b*batch_stride_y + m*ldy + n]; ldy >= N.
- * M <= 8 takes the bandwidth-bound decode path (one pass over the right operand).
+ * With MX_LAYOUT_FRAGMENT, M <= 8 takes the bandwidth-bound decode path (one pass over the
+ * right operand); MX_LAYOUT_MATRIX runs the tiled kernel whatever M is.
  */
 MX_API mx_status mx_gemm(int64_t batch, int64_t M, int64_t N, int64_t K, const void* A_packed, mx_format fa,
                   const void* B_packed, mx_format fb, int32_t layout, float* Y, int64_t ldy,
@@ -278,7 +282,7 @@ MX_API mx_status mx_gemm_q(int64_t batch, int64_t M, int64_t N, int64_t K, const
  * accumulation error of S times scale); a probability that close to a rounding tie of the quantizer,
  * or a block maximum that close to a power of two, can take the neighbouring mantissa or exponent.
  * Blocks of P^ whose elements are below 2^-126 count as zero.
- * Two-row blocks (block_rows = 2, the paper's own block shape, Section 3.1) are taken for every tensor:
+ * Two-row blocks (block_rows = 2, the paper's own block shape, Section 3, the MASE IR example; Section 4.1) are taken for every tensor:
  * the packed operands carry their exponents inside the elements, so fq, fk, fv only need sizes that
  * hold whole pairs (Sq for Q, Sk for K, D for V^T); with fp.block_rows = 2 (Sq even) queries 2t and
  * 2t+1 share the exponent of each block of 16 probabilities.
@@ -294,14 +298,25 @@ MX_API mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t D, 
 /*
  * Linear layer on fp32 activations for decode (M <= 8): quantizes x [M x K] with fx
  * on the fly (same arithmetic as mx_quantize, axis 1), then the product above
- * against B_packed [N x K].  The result equals mx_quantize + mx_pack + mx_gemm.
- * A_scratch: device buffer of mx_packed_bytes(1, M, K, fx, layout) bytes, 256-byte
- * aligned, for the packed activations (caller-owned, may be reused; its content after the call is
- * unspecified: for one or two rows the kernel quantizes straight into on-chip memory).
+ * against B_packed [N x K] (Section 3.2: quantize the input, then the operator).  The result
+ * equals mx_quantize + mx_pack + mx_gemm.  One launch when x is 16-byte aligned, row_stride a
+ * multiple of 4 and fx.block_rows = 1: the weights are split over column groups and K slices so that
+ * every compute unit streams its share once, each workgroup quantizes only its slice of x, and the
+ * slices' partial sums are added in slice order by the last workgroup to finish (the result does not
+ * depend on the order of arrival).  Otherwise two launches (quantize, then the decode product).
+ * workspace: device buffer of mx_linear_workspace_bytes(M, K, N, fx, fb, layout) bytes, 256-byte
+ *   aligned, caller-owned.  Its first 16384 bytes are arrival counters: they must be zero when the call
+ *   starts and every call leaves them zero again, so a buffer that was zero-filled once serves call after
+ *   call, also for other shapes it is large enough for.  The rest (partial sums, packed activations) needs
+ *   no initial value and holds nothing of use afterwards.  Calls that may overlap in time (different
+ *   streams) need a workspace each.
+ * Y: device fp32, 4-byte aligned, element (m, n) at Y[m*ldy + n]; B_packed 256-byte aligned.
  * fx.block_rows = 2 (rows 2p and 2p+1 of x share their exponents) needs an even M.
  */
+MX_API size_t mx_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, mx_format fx, mx_format fb,
+                                        int32_t layout);
 MX_API mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
-                    void* A_scratch, const void* B_packed, int64_t N, mx_format fb, int32_t layout,
+                    void* workspace, const void* B_packed, int64_t N, mx_format fb, int32_t layout,
                     float* Y, int64_t ldy, void* stream);
 
 #ifdef __cplusplus

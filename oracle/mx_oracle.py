@@ -2,9 +2,12 @@
 
 Nothing in the GPU library imports this module; only the tests, the smoke check
 and the CPU-baseline leg of the benchmark do.  Every function here only
-marshals numpy arrays into the plain C routines; the arithmetic (and the
-statement of what the paper fixes and what is a reading of it) lives in the C
-file.
+marshals numpy arrays into the plain C routines of the C file, which holds the
+arithmetic of the quantizers, the bit packing, the width cast and the product
+(and the statement of what the paper fixes and what is a reading of it).  Three
+compositions of those routines are written here in numpy: ``linear_q`` (product,
+bias, output quantizer), ``attention`` (the four steps of an MXInt attention
+head) and the regrouping of rows for two-row blocks (``block_rows``).
 
 Format arguments follow Section 4.1 of the paper: ``block`` elements share one
 ``e``-bit exponent; ``w`` is the stored width of an element, i.e. the paper's
@@ -239,7 +242,7 @@ def linear_q(x: np.ndarray, wt: np.ndarray, bias: Optional[np.ndarray], block: i
 
 def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, wk: int, wp: int, wv: int,
               scale: float, e: int = 8, rounding: int = RNE, rows: Optional[Tuple[int, int]] = None,
-              block_rows: int = 1):
+              block_rows: int = 1, e_pv: Optional[int] = None):
     """One head of attention with every matrix product taken in MXInt (Fig. 1: the two products of the
     attention layer have both operands quantized; Section 3.2: an emulated operator quantizes its inputs
     and computes on the quantized values; softmax itself stays in floating point).
@@ -252,10 +255,14 @@ def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, 
     Returns O float64 [Sq,D] and a dict with the intermediate values the tests derive tolerances from:
     S, S_mag (sum_b |term_b| of step 1), P (float64), pq/pe and vq/ve (the quantized operands of step 4)
     and O_mag.  rows=(begin,end) restricts the query rows that are computed (others are NaN).
-    block_rows=2: every tensor in the paper's two-dimensional block shape (block, 2) (Section 3.1) -- two
+    block_rows=2: every tensor in the paper's two-dimensional block shape (block, 2) (Section 3, the MASE IR example; Section 4.1) -- two
     neighbouring rows of the matrix that is quantized share their exponents: two queries (Q, P), two keys
     (K), two columns of V (the rows of V^T).  pe and ve then hold one exponent row per matrix row (each
-    shared row repeated), as the product takes them."""
+    shared row repeated), as the product takes them.
+    e_pv: exponent width of P and V, the operands of the second product (default: e, the width of Q and K;
+    Section 4.1 lets the exponent width be chosen per tensor even though the paper then fixes 8 for all)."""
+    if e_pv is None:
+        e_pv = e
     Q = np.ascontiguousarray(Q, np.float32)
     K = np.ascontiguousarray(K, np.float32)
     V = np.ascontiguousarray(V, np.float32)
@@ -270,13 +277,13 @@ def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, block: int, wq: int, 
     Z = Z - Z.max(axis=1, keepdims=True)
     P = np.exp(Z)
     P = P / P.sum(axis=1, keepdims=True)
-    pq, pe = quantize(P.astype(np.float32), block, wp, e, rounding, block_rows=R)
+    pq, pe = quantize(P.astype(np.float32), block, wp, e_pv, rounding, block_rows=R)
     if R == 1:
-        vq, ve = quantize(V, block, wv, e, rounding, axis=0)      # the quantization of V^T: [D, Sk]
+        vq, ve = quantize(V, block, wv, e_pv, rounding, axis=0)   # the quantization of V^T: [D, Sk]
     else:
-        vq, ve = quantize(np.ascontiguousarray(V.T), block, wv, e, rounding, block_rows=R)
+        vq, ve = quantize(np.ascontiguousarray(V.T), block, wv, e_pv, rounding, block_rows=R)
     pe, ve = row_exps(pe, R), row_exps(ve, R)
-    Osub, o_mag = gemm(pq, pe, wp, vq, ve, wv, block, e, want_mag=True)
+    Osub, o_mag = gemm(pq, pe, wp, vq, ve, wv, block, e_pv, want_mag=True)
     O = np.full((Q.shape[0], V.shape[1]), np.nan, np.float64)
     O[r0:r1] = Osub
     return O, {"S": S, "S_mag": s_mag, "P": P, "pq": pq, "pe": pe, "vq": vq, "ve": ve, "O_mag": o_mag,

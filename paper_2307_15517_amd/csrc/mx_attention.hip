@@ -469,7 +469,8 @@ extern "C" mx_status mx_attention(int64_t batch, int64_t Sq, int64_t Sk, int64_t
         return MX_ERR_UNSUPPORTED;
     if (fq.block != 16 || fv.block != 16 || (fp.block != 16 && fp.block != 32) || D > 128) return MX_ERR_UNSUPPORTED;
     if (batch == 0 || Sq == 0) return MX_OK;
-    if (!Q_packed || !K_packed || !Vt_packed || !O) return MX_ERR_BAD_ARG;
+    if (!Q_packed || !K_packed || !Vt_packed || !O || ((uintptr_t)O & 3)) return MX_ERR_BAD_ARG;
+    if (batch > 1 && o_batch_stride < (Sq - 1) * ldo + D) return MX_ERR_BAD_ARG;      // heads would overlap
     if (((uintptr_t)Q_packed & 255) || ((uintptr_t)K_packed & 255) || ((uintptr_t)Vt_packed & 255)) return MX_ERR_BAD_ARG;
     const BfGeom gq = bf_geom(Sq, D), gk = bf_geom(Sk, D), gv = bf_geom(D, Sk);
     AttnArgs g;

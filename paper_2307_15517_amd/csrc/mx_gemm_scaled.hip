@@ -120,13 +120,18 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
-    // Workgroup i runs on XCD i % 8, each with its own L2.  Give every XCD one contiguous range of
-    // tiles, numbered with the M tile fastest, so that the tiles resident on an XCD at one time share
-    // their operand rows (all M tiles of a few N tiles) and hit in that L2.
+    // Workgroup i runs on XCD i % 8, each with its own L2.  Give every XCD one contiguous range of tiles of
+    // an order in which consecutive tiles form a compact block of the tile grid (below), so that the tiles
+    // resident on an XCD at one time share rows of both operands in that L2.
     const int64_t tiles = (int64_t)g.tiles_m * g.tiles_n, per_xcd = (tiles + 7) / 8;
     const int64_t tile = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (tile >= tiles) return;
-    const int64_t bm = tile % g.tiles_m, bn = tile / g.tiles_m;
+    // bands of eight M tiles, N fastest across a band, M fastest inside it: a run of consecutive tiles is a
+    // compact block of the tile grid
+    const int64_t hm = g.tiles_m < 8 ? g.tiles_m : 8;
+    const int64_t band = tile / (hm * g.tiles_n), rr = tile - band * hm * g.tiles_n;
+    const int64_t hb = (g.tiles_m - band * hm) < hm ? (g.tiles_m - band * hm) : hm;
+    const int64_t bn = rr / hb, bm = band * hm + (rr - bn * hb);
     const int64_t bz = blockIdx.y;
     const uint8_t* Abase = g.A + bz * g.matrixA;
     const uint8_t* Bbase = g.B + bz * g.matrixB;

@@ -10,61 +10,12 @@
 // every second block in fp32 and the halves meet in one cross-lane add at the end.  The
 // activations are unpacked to int8 once per workgroup into LDS and read back as broadcasts.
 #include "mx_gemm.h"
+#include "mx_frag.h"
 
 namespace mx {
 namespace {
 
-template <int W, int B> struct Piece { static constexpr int kDw = B * W / 16; };
-
-template <int NDW>
-__device__ __forceinline__ void load_dwords(const uint8_t* p, uint32_t* out) {
-    if constexpr (NDW % 4 == 0) {
-#pragma unroll
-        for (int d = 0; d < NDW / 4; ++d) {
-            uint4 v = reinterpret_cast<const uint4*>(p)[d];
-            out[4 * d] = v.x; out[4 * d + 1] = v.y; out[4 * d + 2] = v.z; out[4 * d + 3] = v.w;
-        }
-    } else if constexpr (NDW % 2 == 0) {
-#pragma unroll
-        for (int d = 0; d < NDW / 2; ++d) {
-            uint2 v = reinterpret_cast<const uint2*>(p)[d];
-            out[2 * d] = v.x; out[2 * d + 1] = v.y;
-        }
-    } else {
-#pragma unroll
-        for (int d = 0; d < NDW; ++d) out[d] = reinterpret_cast<const uint32_t*>(p)[d];
-    }
-}
-
-// Half-block j of a lane piece of the right operand -> B/2 int8 in B/8 dwords (times 16 for W = 4).
-template <int W, int B> struct UnpackB {
-    static constexpr int kScaleLog2 = (W == 4) ? 4 : 0;
-    __device__ __forceinline__ static void run(const uint32_t* piece, int j, uint32_t* out) {
-        constexpr int kOut = B / 8;
-        if constexpr (W == 8) {
-#pragma unroll
-            for (int d = 0; d < kOut; ++d) out[d] = piece[j * kOut + d];
-        } else if constexpr (W == 4) {
-#pragma unroll
-            for (int d = 0; d < kOut / 2; ++d) {
-                const uint32_t x = piece[j * (kOut / 2) + d];
-                out[2 * d] = (x << 4) & 0xF0F0F0F0u;
-                out[2 * d + 1] = x & 0xF0F0F0F0u;
-            }
-        } else {
-#pragma unroll
-            for (int d = 0; d < kOut; ++d) {
-                uint32_t o = 0;
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int bit = (j * (B / 2) + d * 4 + t) * W;
-                    o |= ((uint32_t)stream_get<W>(piece, bit) & 0xFFu) << (8 * t);
-                }
-                out[d] = o;
-            }
-        }
-    }
-};
+template <int W, int B> using UnpackB = Unpack<W, B>;
 
 // Mantissa t of half-block j of a left-operand lane piece (runtime width), sign-extended.
 __device__ __forceinline__ int piece_get(const uint8_t* piece, int j, int t, int w, int B) {

@@ -2,6 +2,7 @@
 // straight into the fragment layout, then the decode kernel of mx_gemm streams the packed weights.
 // The quantizer arithmetic is the one of mx_quantize (Section 4.1 format; Section 3.2 emulation
 // semantics: quantize the input, then the operator).
+#include "mx_decode.h"
 #include "mx_gemm.h"
 
 namespace mx {
@@ -201,8 +202,18 @@ mx_status quantize_pack_fragment(const float* x, int64_t batch, int64_t rows, in
 
 using namespace mx;
 
+// Bytes of the workspace mx_linear needs for this call: arrival counters, partial sums of the K slices, and the
+// packed activations of the two-launch form.  0 on a bad argument.
+extern "C" size_t mx_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, mx_format fx, mx_format fb,
+                                            int32_t layout) {
+    if (!format_ok_gemm(fx) || !format_ok_gemm(fb) || fx.block != fb.block || layout != MX_LAYOUT_FRAGMENT) return 0;
+    if (M < 0 || M > 8 || N < 0 || K < 0 || K % fx.block != 0) return 0;
+    const DecodePlan p = decode_plan(M, K, N, fb.block, fb.mant_bits);
+    return (size_t)(decode_packed_offset(p) + frag_geom(M, K, fx.block, fx.mant_bits).matrix);
+}
+
 extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
-                               void* A_scratch, const void* B_packed, int64_t N, mx_format fb,
+                               void* workspace, const void* B_packed, int64_t N, mx_format fb,
                                int32_t layout, float* Y, int64_t ldy, void* stream) {
     if (!format_ok_quant(fx) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
     if (fx.block != fb.block || fx.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
@@ -212,19 +223,29 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
     if (M < 0 || N < 0 || K < 0 || K % fx.block != 0 || row_stride < K || ldy < N) return MX_ERR_BAD_ARG;
     if (M > 8) return MX_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return MX_OK;
-    if (K > 0 && (!x || !A_scratch || !B_packed)) return MX_ERR_BAD_ARG;
-    if (((uintptr_t)x & 3) || ((uintptr_t)A_scratch & 255)) return MX_ERR_BAD_ARG;
+    if (!Y || ((uintptr_t)Y & 3)) return MX_ERR_BAD_ARG;
+    if (K > 0 && (!x || !workspace || !B_packed)) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)x & 3) || ((uintptr_t)workspace & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
-    if (K > 0 && M <= 2 && fx.block_rows == 1 && ((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0) {
-        // one launch: the dot-product decode kernel quantizes the activations on its way into LDS
-        // (same arithmetic, same accumulation order as the two-launch form); A_scratch is not touched
-        const GemmArgs g = fragment_args(M, N, K, A_scratch, fx, B_packed, fb, Y, ldy, M * ldy);
+    const DecodePlan p = decode_plan(M, K, N, fb.block, fb.mant_bits);
+    const bool fused_ok = K > 0 && fx.block_rows == 1 && ((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0;
+    if (fused_ok && M <= 2) {
+        // one launch, one workgroup per column group: the dot-product decode kernel quantizes the activations on
+        // its way into LDS; nothing passes between workgroups, the workspace is not touched
+        const GemmArgs g = fragment_args(M, N, K, nullptr, fx, B_packed, fb, Y, ldy, M * ldy);
         const mx_status s = gemv_dot(g, fx.mant_bits, fb.mant_bits, fx.block, 1, st, x, row_stride, &fx);
         if (s != MX_ERR_UNSUPPORTED) return s;
     }
+    if (fused_ok && M > 2 && p.ok) {
+        // one launch: column groups x K slices, the activations of a slice quantized inside the kernel
+        const mx_status s = linear_decode(x, M, K, row_stride, fx, workspace, B_packed, N, fb, Y, ldy, st);
+        if (s != MX_ERR_UNSUPPORTED) return s;
+    }
+    // two launches: quantize into the fragment layout, then the decode product of mx_gemm
+    void* packed = (uint8_t*)workspace + decode_packed_offset(p);
     if (K > 0) {
-        mx_status s = run_lq(x, 1, M, M, K, row_stride, 0, fx, (uint8_t*)A_scratch, st);
+        mx_status s = run_lq(x, 1, M, M, K, row_stride, 0, fx, (uint8_t*)packed, st);
         if (s != MX_OK) return s;
     }
-    return mx_gemm(1, M, N, K, A_scratch, fx, B_packed, fb, layout, Y, ldy, M * ldy, stream);
+    return mx_gemm(1, M, N, K, packed, fx, B_packed, fb, layout, Y, ldy, M * ldy, stream);
 }

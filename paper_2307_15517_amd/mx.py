@@ -23,7 +23,8 @@ MX_LAYOUT_MATRIX = 1
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
            "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0", "mx_unpack",
            "mx_gemm",
-           "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat")
+           "mx_gemm_q", "mx_attention", "mx_linear", "mx_linear_workspace_bytes", "mx_quantize_minifloat",
+           "mx_dequantize_minifloat")
 
 
 class mx_format(ctypes.Structure):
@@ -84,6 +85,8 @@ def load() -> ctypes.CDLL:
     lib.mx_quantize_minifloat.argtypes = [vp, i64, i64, i64, i64, i64, mx_minifloat_format, vp, vp, vp]
     lib.mx_dequantize_minifloat.argtypes = [vp, vp, i64, i64, i64, mx_minifloat_format, vp, vp]
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
+    lib.mx_linear_workspace_bytes.argtypes = [i64, i64, i64, mx_format, mx_format, i32]
+    lib.mx_linear_workspace_bytes.restype = sz
     for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0",
                  "mx_unpack", "mx_gemm",
                  "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat"):
@@ -232,9 +235,14 @@ def mx_dequantize_minifloat(codes, shared, batch, rows, cols, f, y, stream=None,
     return s
 
 
-def mx_linear(x, M, K, row_stride, fx, A_scratch, B_packed, N, fb, layout, Y, ldy, stream=None,
+def mx_linear_workspace_bytes(M: int, K: int, N: int, fx: mx_format, fb: mx_format,
+                              layout: int = MX_LAYOUT_FRAGMENT) -> int:
+    return int(load().mx_linear_workspace_bytes(M, K, N, fx, fb, layout))
+
+
+def mx_linear(x, M, K, row_stride, fx, workspace, B_packed, N, fb, layout, Y, ldy, stream=None,
               check: bool = True) -> int:
-    s = load().mx_linear(_p(x), M, K, row_stride, fx, _p(A_scratch), _p(B_packed), N, fb, layout, _p(Y),
+    s = load().mx_linear(_p(x), M, K, row_stride, fx, _p(workspace), _p(B_packed), N, fb, layout, _p(Y),
                          ldy, _stream(stream))
     if check:
         _raise(s, "mx_linear")
@@ -322,6 +330,11 @@ def unpack(packed: torch.Tensor, batch: int, rows: int, cols: int, f: mx_format,
     exps = torch.empty(mx_exps_bytes(batch, rows, cols, f), dtype=torch.uint8, device=packed.device)
     mx_unpack(packed, batch, rows, cols, f, layout, mant, exps)
     return mant, exps
+
+
+def linear_workspace(M: int, K: int, N: int, fx: mx_format, fb: mx_format, device) -> torch.Tensor:
+    """A zero-filled workspace for mx_linear (the arrival counters at its start must be zero before the first call)."""
+    return torch.zeros(max(1, mx_linear_workspace_bytes(M, K, N, fx, fb)), dtype=torch.uint8, device=device)
 
 
 def gemm(A_packed: torch.Tensor, fa: mx_format, B_packed: torch.Tensor, fb: mx_format, M: int, N: int,

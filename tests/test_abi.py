@@ -98,8 +98,42 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert g(M=0) == mx.MX_OK
     assert mx.mx_linear(256, 9, 64, 64, f, 256, 512, 32, mx.fmt(32, 4), 0, 1024, 32, stream=0,
                         check=False) == mx.MX_ERR_UNSUPPORTED            # decode path is M <= 8
+    # mx_linear rejects what its kernels would dereference: output, workspace and weights (all return before a launch)
+    lin = lambda **kw: mx.mx_linear(kw.get("x", 256), kw.get("M", 4), 64, 64, f, kw.get("ws", 256), kw.get("B", 512), 32,
+                                    mx.fmt(32, 4), 0, kw.get("Y", 1024), kw.get("ldy", 32), stream=0, check=False)
+    assert lin(Y=0) == mx.MX_ERR_BAD_ARG
+    assert lin(Y=1026) == mx.MX_ERR_BAD_ARG                              # not 4-byte aligned
+    assert lin(B=516) == mx.MX_ERR_BAD_ARG                               # not 256-byte aligned
+    assert lin(B=0) == mx.MX_ERR_BAD_ARG
+    assert lin(ws=0) == mx.MX_ERR_BAD_ARG
+    assert lin(ws=260) == mx.MX_ERR_BAD_ARG
+    assert lin(x=0) == mx.MX_ERR_BAD_ARG
+    assert lin(ldy=16) == mx.MX_ERR_BAD_ARG
+    assert lin(M=0) == mx.MX_OK
+    # mx_attention: output alignment, and heads that would overlap
+    f16 = mx.fmt(16, 8)
+    att = lambda **kw: mx.mx_attention(kw.get("batch", 2), 32, 32, 64, 256, f16, 512, f16, 768, f16, f16, 0.125,
+                                       mx.MX_LAYOUT_MATRIX, kw.get("O", 1024), 64, kw.get("obs", 32 * 64), stream=0,
+                                       check=False)
+    assert att(O=1026) == mx.MX_ERR_BAD_ARG
+    assert att(O=0) == mx.MX_ERR_BAD_ARG
+    assert att(obs=31 * 64 + 63) == mx.MX_ERR_BAD_ARG                    # batch stride below (Sq-1)*ldo + D
+    assert att(batch=0) == mx.MX_OK
     with pytest.raises(mx.MxError):
         mx.mx_quantize(0, 1, 4, 64, 64, 0, 1, f, 256, 256, stream=0)
+
+
+def test_linear_workspace_bytes():
+    """Workspace of mx_linear: counters + partial sums of the K slices + packed activations; 0 on bad arguments."""
+    fa, fb = mx.fmt(16, 8), mx.fmt(16, 4)
+    small = mx.mx_linear_workspace_bytes(1, 5120, 5120, fa, fb)
+    big = mx.mx_linear_workspace_bytes(8, 5120, 13824, fa, fb)
+    assert small >= 16384 + mx.mx_packed_bytes(1, 1, 5120, fa) and small % 256 == 0
+    assert big > small and big < (64 << 20)
+    assert mx.mx_linear_workspace_bytes(9, 5120, 5120, fa, fb) == 0
+    assert mx.mx_linear_workspace_bytes(4, 5000, 5120, fa, fb) == 0      # K not a whole number of blocks
+    assert mx.mx_linear_workspace_bytes(4, 5120, 5120, fa, mx.fmt(32, 4)) == 0
+    assert mx.mx_linear_workspace_bytes(4, 5120, 5120, fa, fb, mx.MX_LAYOUT_MATRIX) == 0
 
 
 def test_struct_layout():

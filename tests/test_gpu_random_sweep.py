@@ -72,7 +72,7 @@ def test_random_decode_linear(seed):
         wt = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
         fa, fb = mx.fmt(block, wx), mx.fmt(block, ww)
         B = mx.quantize_pack(T.dev(wt), fb, mx.MX_LAYOUT_FRAGMENT)
-        scratch = torch.zeros(mx.mx_packed_bytes(1, M, K, fa), dtype=torch.uint8, device=T.DEV)
+        scratch = mx.linear_workspace(M, K, N, fa, fb, T.DEV)
         y = torch.full((M, N), 3.0, dtype=torch.float32, device=T.DEV)
         xv = T.dev(xp)[:, off:off + K]
         mx.mx_linear(xv, M, K, K + 4, fa, scratch, B, N, fb, mx.MX_LAYOUT_FRAGMENT, y, N)

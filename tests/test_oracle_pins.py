@@ -626,8 +626,52 @@ def test_attention_steps_against_library_routines():
     assert np.array_equal(O2[8:16], O[8:16]) and np.all(np.isnan(O2[:8])) and np.all(np.isnan(O2[16:]))
 
 
+def test_attention_narrow_exponent_for_p_and_v():
+    """A separate exponent width for P and V (e_pv).  Hand-worked: with e_pv = 4 the smallest block exponent
+    is -7, so a block of probabilities whose maximum is 2^-12 is held with exponent -7 -- at width 8 its
+    mantissas are p * 2^13 = 2, exact -- and a block whose maximum is 2^-20 loses everything but does not
+    wrap.  V saturates the other way: 1000 needs exponent 9 and e_pv = 4 stops at 8, so the mantissa clamps
+    at 127 * 2^(8-6) = 508.  Then each step against routines that are not the oracle's: the second product is
+    the float matmul of the operands quantized with e_pv, and e_pv = e reproduces the default call."""
+    from scipy.special import softmax
+    Sk, D = 32, 16
+    K = np.zeros((Sk, D), np.float32)
+    K[:, 0] = [0.0] + [-12.0] * 15 + [-20.0] * 16          # log2 of the unnormalised probabilities
+    Q = np.zeros((2, D), np.float32)
+    Q[:, 0] = 1.0
+    V = np.zeros((Sk, D), np.float32)
+    V[0, 0], V[1, 0], V[16, 0] = 1000.0, 1.0, 1.0
+    O, info = orc.attention(Q, K, V, 16, 8, 8, 8, 8, scale=math.log(2.0), e_pv=4)
+    Z = 1.0 + 15 * 2.0 ** -12 + 16 * 2.0 ** -20
+    assert np.allclose(info["P"][0, :2], [1 / Z, 2.0 ** -12 / Z], rtol=1e-14)
+    assert info["pe"][0].tolist() == [7 - 1, 0]                          # E = -1 (p0 just below 1); clamped at -7
+    assert info["pq"][0, 16:].tolist() == [0] * 16                      # 2^-20 * 2^13 rounds to 0
+    assert info["ve"][0].tolist() == [15, 7]                             # E = 8 (clamped from 9); E = 0
+    assert info["vq"][0, 0] == 127 and info["vq"][0, 1] == 0 and info["vq"][0, 16] == 64
+    p0 = float(info["pq"][0, 0]) * 2.0 ** (-1 - 6)
+    p1 = float(info["pq"][0, 1]) * 2.0 ** (-1 - 6)
+    assert info["pq"][0, 1] == 0                                         # 2^-12 shares the block of p0: below half a step
+    assert O[0, 0] == p0 * 508.0 + p1 * 0.0
+    rng = np.random.default_rng(11)
+    Sq, Sk, D = 16, 64, 32
+    Q = rng.standard_normal((Sq, D)).astype(np.float32)
+    K = rng.standard_normal((Sk, D)).astype(np.float32)
+    V = (rng.standard_normal((Sk, D)) * 300.0).astype(np.float32)
+    O, info = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=1.0, e_pv=4)
+    P = softmax(info["S"], axis=1)
+    pq, pe = orc.quantize(P.astype(np.float32), 16, 5, 4)
+    vq, ve = orc.quantize(V, 16, 4, 4, axis=0)
+    assert np.array_equal(pq, info["pq"]) and np.array_equal(pe, info["pe"])
+    assert np.array_equal(vq, info["vq"]) and np.array_equal(ve, info["ve"])
+    assert pe.min() == 0 and ve.max() == 15                              # both clamps are reached here
+    assert np.allclose(O, orc.dequantize(pq, pe, 16, 5, 4) @ orc.dequantize(vq, ve, 16, 4, 4).T, rtol=1e-12, atol=1e-12)
+    Oa, _ = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=1.0, e_pv=8)
+    Ob, _ = orc.attention(Q, K, V, 16, 7, 6, 5, 4, scale=1.0)
+    assert np.array_equal(Oa, Ob) and not np.array_equal(Oa, O)
+
+
 def test_attention_two_row_blocks_pairs_of_equal_rows_change_nothing():
-    """The paper's block shape (block, 2) (Section 3.1) in the attention layer.  When rows 2i and 2i+1 of
+    """The paper's block shape (block, 2) (Section 3, the MASE IR example; Section 4.1) in the attention layer.  When rows 2i and 2i+1 of
     every quantized matrix are equal (queries, keys, and the columns of V, which are the rows of V^T), a
     two-row block holds the same values twice, so its maximum, exponent and mantissas are those of the
     one-row blocks: the outputs are identical."""
