@@ -319,6 +319,23 @@ MX_API mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_str
                     void* workspace, const void* B_packed, int64_t N, mx_format fb, int32_t layout,
                     float* Y, int64_t ldy, void* stream);
 
+/*
+ * mx_linear for callers that cannot allocate or pass device memory of their own for it: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic, kernels and
+ * results as mx_linear, without the workspace argument: the workspace is an array the library holds in
+ * device memory itself, mx_linear_static_workspace_max() bytes (8 MiB) on every GPU the library is used on,
+ * from load until the process ends.  The call allocates and frees nothing; it first clears the arrival
+ * counters with a small kernel on `stream`.  MX_ERR_UNSUPPORTED when
+ * mx_linear_workspace_bytes(M, K, N, fx, fb, layout) exceeds that size (the LLaMA-13B decode shapes need under
+ * 4 MiB); MX_ERR_DEVICE when the array's address cannot be obtained.  The device of `stream` must be the
+ * current device.  Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU
+ * (different streams, different host threads) race -- give those mx_linear with a workspace each.
+ */
+MX_API size_t mx_linear_static_workspace_max(void);
+MX_API mx_status mx_linear_static_workspace(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
+                                     const void* B_packed, int64_t N, mx_format fb, int32_t layout,
+                                     float* Y, int64_t ldy, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -212,9 +212,12 @@ extern "C" size_t mx_linear_workspace_bytes(int64_t M, int64_t K, int64_t N, mx_
     return (size_t)(decode_packed_offset(p) + frag_geom(M, K, fx.block, fx.mant_bits).matrix);
 }
 
-extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
-                               void* workspace, const void* B_packed, int64_t N, mx_format fb,
-                               int32_t layout, float* Y, int64_t ldy, void* stream) {
+namespace {
+
+// Argument checks of mx_linear that need no workspace.  MX_OK means "go on"; *done is set when there is nothing to do.
+mx_status linear_check(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx, const void* B_packed,
+                       int64_t N, mx_format fb, int32_t layout, float* Y, int64_t ldy, bool* done) {
+    *done = false;
     if (!format_ok_quant(fx) || !format_ok_quant(fb)) return MX_ERR_BAD_ARG;
     if (fx.block != fb.block || fx.exp_bits != fb.exp_bits) return MX_ERR_BAD_ARG;
     if (!format_ok_gemm(fx)) return MX_ERR_UNSUPPORTED;
@@ -222,10 +225,17 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
     if (layout != MX_LAYOUT_FRAGMENT) return layout == MX_LAYOUT_MATRIX ? MX_ERR_UNSUPPORTED : MX_ERR_BAD_ARG;
     if (M < 0 || N < 0 || K < 0 || K % fx.block != 0 || row_stride < K || ldy < N) return MX_ERR_BAD_ARG;
     if (M > 8) return MX_ERR_UNSUPPORTED;
-    if (M == 0 || N == 0) return MX_OK;
+    if (M == 0 || N == 0) { *done = true; return MX_OK; }
     if (!Y || ((uintptr_t)Y & 3)) return MX_ERR_BAD_ARG;
-    if (K > 0 && (!x || !workspace || !B_packed)) return MX_ERR_BAD_ARG;
-    if (((uintptr_t)x & 3) || ((uintptr_t)workspace & 255) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
+    if (K > 0 && (!x || !B_packed)) return MX_ERR_BAD_ARG;
+    if (((uintptr_t)x & 3) || ((uintptr_t)B_packed & 255)) return MX_ERR_BAD_ARG;
+    return MX_OK;
+}
+
+// The work of mx_linear on checked arguments and a workspace whose counters are zero.
+mx_status linear_run(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx, void* workspace,
+                     const void* B_packed, int64_t N, mx_format fb, int32_t layout, float* Y, int64_t ldy,
+                     void* stream) {
     hipStream_t st = (hipStream_t)stream;
     const DecodePlan p = decode_plan(M, K, N, fb.block, fb.mant_bits);
     const bool fused_ok = K > 0 && fx.block_rows == 1 && ((uintptr_t)x & 15) == 0 && (row_stride & 3) == 0;
@@ -248,4 +258,59 @@ extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row
         if (s != MX_OK) return s;
     }
     return mx_gemm(1, M, N, K, packed, fx, B_packed, fb, layout, Y, ldy, M * ldy, stream);
+}
+
+// Device memory the library owns, for callers that cannot hand over a workspace: one array per GPU, there from the
+// moment the library is loaded until the process ends.  Host code never uses this name as an address -- it is the
+// host-side stand-in of a device symbol; the address on the current device comes from hipGetSymbolAddress (below).
+constexpr int64_t kStaticWorkspaceBytes = 8 << 20;
+static __device__ __align__(256) uint8_t static_workspace[kStaticWorkspaceBytes];
+
+__global__ void clear_counters_kernel(uint32_t* counters) {
+    for (int64_t i = threadIdx.x; i < kDecodeCounterBytes / 4; i += blockDim.x) counters[i] = 0u;
+}
+
+// Address of static_workspace on the current device, looked up once per device.
+void* static_workspace_ptr() {
+    static std::atomic<void*> ptrs[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) return nullptr;
+    void* p = ptrs[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(static_workspace)) != hipSuccess || !p) return nullptr;
+    ptrs[dev].store(p, std::memory_order_release);
+    return p;
+}
+
+}  // namespace
+
+extern "C" mx_status mx_linear(const float* x, int64_t M, int64_t K, int64_t row_stride, mx_format fx,
+                               void* workspace, const void* B_packed, int64_t N, mx_format fb,
+                               int32_t layout, float* Y, int64_t ldy, void* stream) {
+    bool done;
+    const mx_status s = linear_check(x, M, K, row_stride, fx, B_packed, N, fb, layout, Y, ldy, &done);
+    if (s != MX_OK || done) return s;
+    if (K > 0 && !workspace) return MX_ERR_BAD_ARG;
+    if ((uintptr_t)workspace & 255) return MX_ERR_BAD_ARG;
+    return linear_run(x, M, K, row_stride, fx, workspace, B_packed, N, fb, layout, Y, ldy, stream);
+}
+
+extern "C" size_t mx_linear_static_workspace_max(void) { return (size_t)kStaticWorkspaceBytes; }
+
+extern "C" mx_status mx_linear_static_workspace(const float* x, int64_t M, int64_t K, int64_t row_stride,
+                                                mx_format fx, const void* B_packed, int64_t N, mx_format fb,
+                                                int32_t layout, float* Y, int64_t ldy, void* stream) {
+    bool done;
+    const mx_status s = linear_check(x, M, K, row_stride, fx, B_packed, N, fb, layout, Y, ldy, &done);
+    if (s != MX_OK || done) return s;
+    const size_t need = mx_linear_workspace_bytes(M, K, N, fx, fb, layout);
+    if (need == 0) return MX_ERR_BAD_ARG;
+    if (need > (size_t)kStaticWorkspaceBytes) return MX_ERR_UNSUPPORTED;      // the shape needs more than the library holds
+    void* ws = static_workspace_ptr();
+    if (!ws) return MX_ERR_DEVICE;
+    // the array keeps what the last call on this GPU left: the counters start every call at zero (a fill kernel,
+    // not a memset node, so that the call can be captured into a graph)
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, (uint32_t*)ws);
+    MX_HIP_LAUNCH_CHECK();
+    return linear_run(x, M, K, row_stride, fx, ws, B_packed, N, fb, layout, Y, ldy, stream);
 }

@@ -23,7 +23,8 @@ MX_LAYOUT_MATRIX = 1
 EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
            "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0", "mx_unpack",
            "mx_gemm",
-           "mx_gemm_q", "mx_attention", "mx_linear", "mx_linear_workspace_bytes", "mx_quantize_minifloat",
+           "mx_gemm_q", "mx_attention", "mx_linear", "mx_linear_workspace_bytes", "mx_linear_static_workspace",
+           "mx_linear_static_workspace_max", "mx_quantize_minifloat",
            "mx_dequantize_minifloat")
 
 
@@ -87,6 +88,9 @@ def load() -> ctypes.CDLL:
     lib.mx_linear.argtypes = [vp, i64, i64, i64, mx_format, vp, vp, i64, mx_format, i32, vp, i64, vp]
     lib.mx_linear_workspace_bytes.argtypes = [i64, i64, i64, mx_format, mx_format, i32]
     lib.mx_linear_workspace_bytes.restype = sz
+    lib.mx_linear_static_workspace.argtypes = [vp, i64, i64, i64, mx_format, vp, i64, mx_format, i32, vp, i64, vp]
+    lib.mx_linear_static_workspace.restype = i32
+    lib.mx_linear_static_workspace_max.argtypes, lib.mx_linear_static_workspace_max.restype = [], sz
     for name in ("mx_quantize", "mx_dequantize", "mx_cast", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0",
                  "mx_unpack", "mx_gemm",
                  "mx_gemm_q", "mx_attention", "mx_linear", "mx_quantize_minifloat", "mx_dequantize_minifloat"):
@@ -247,6 +251,19 @@ def mx_linear(x, M, K, row_stride, fx, workspace, B_packed, N, fb, layout, Y, ld
     if check:
         _raise(s, "mx_linear")
     return s
+
+
+def mx_linear_static_workspace(x, M, K, row_stride, fx, B_packed, N, fb, layout, Y, ldy, stream=None,
+                               check: bool = True) -> int:
+    s = load().mx_linear_static_workspace(_p(x), M, K, row_stride, fx, _p(B_packed), N, fb, layout, _p(Y), ldy,
+                                          _stream(stream))
+    if check:
+        _raise(s, "mx_linear_static_workspace")
+    return s
+
+
+def mx_linear_static_workspace_max() -> int:
+    return int(load().mx_linear_static_workspace_max())
 
 
 def bound(name: str, *args, stream=None):
