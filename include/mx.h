@@ -87,6 +87,18 @@ typedef enum { MX_OK = 0, MX_ERR_BAD_ARG = 1, MX_ERR_UNSUPPORTED = 2, MX_ERR_DEV
  *       one-code operands) and K to 256.  Restriction: exponent bytes above 250 (|x| >= 2^124 at
  *       e = 8) are not representable next to the +4 offset of the high code; such blocks give
  *       unspecified products.
+ *       Accuracy of products in this layout (both block forms): mantissa products and their sums inside a
+ *       block are exact, but the matrix instruction aligns the running fp32 sum to the largest SINGLE product
+ *       it adds and keeps 24 bits below that, not below the block sums.  A block whose large products cancel
+ *       can therefore push out low bits that much smaller blocks had contributed.  Guaranteed for any in-range
+ *       input:  |err| <= 1e-5 * sum_blocks |block term|  +  1e-6 * sum_k |product_k|.  The first term alone
+ *       holds whenever, for an output element, the exponent sums Ea + Eb of its blocks span at most
+ *       25 - wa - wb binades (13 for 8-bit by 4-bit operands: a product has at most wa + wb - 2 bits, so
+ *       nothing is pushed out then) -- and it
+ *       holds on LLM-shaped data (heavy tails, outlier channels), where products do not cancel inside blocks
+ *       to that degree.  The weaker bound is still tighter than that of a float product of the dequantized
+ *       operands, Section 3.2's emulated operator.  Callers that need the first term alone on arbitrary data
+ *       use MX_LAYOUT_FRAGMENT.
  *       Block 16 (that instruction scales runs of 32, not 16): every element is stored as the
  *       bfloat16 number mantissa * 2^exponent, which is exact, 16 bits per element plus the
  *       exponent bytes; rows are padded to 32 and K to 64.  Restriction: nonzero elements must be
@@ -230,9 +242,11 @@ MX_API mx_status mx_unpack(const void* packed, int64_t batch, int64_t rows, int6
  * MXInt x MXInt product (Section 3.2, the MXInt dot-product operator):
  *   Y[b][m][n] = sum over K-blocks j of
  *        ( sum_{k in block j} qa[m][k] * qb[n][k] )  *  2^(Ea[m][j] + Eb[n][j] - (wa-2) - (wb-2))
- * The inner sum is exact integer arithmetic on the matrix cores; each block's
- * scaled value is added into an fp32 accumulator.  Both operands come from mx_pack
- * in the same layout.  The left operand is M x K; the right operand is given as
+ * The inner sum is exact (integer matrix instructions on MX_LAYOUT_FRAGMENT; small integers in
+ * float codes on MX_LAYOUT_MATRIX); the blocks' scaled values are added in fp32.  Error against the
+ * exact value: MX_LAYOUT_FRAGMENT |err| <= 1e-5 * sum_blocks |block term| for any input;
+ * MX_LAYOUT_MATRIX the bound stated at the layout (an extra 1e-6 * sum_k |product_k| on
+ * adversarial exponent spreads).  Both operands come from mx_pack in the same layout.  The left operand is M x K; the right operand is given as
  * N x K (one row per output column, like torch.nn.Linear.weight).
  * fa.block == fb.block and fa.exp_bits == fb.exp_bits are required.
  * Y: fp32, element (b, m, n) at Y[b*batch_stride_y + m*ldy + n]; ldy >= N.

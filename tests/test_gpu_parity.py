@@ -452,8 +452,8 @@ def test_gemm_llama7b_reduced_m256_full_output():
 @pytest.mark.parametrize("idx", [0, 1, 2])
 def test_gemm_llama7b_full_size_sampled_rows(idx):
     case = inputs.llama7b_prefill()[idx]
-    # the benchmark's launch configuration (M = 2048); the oracle computes a 48-row window
-    say("gemm", case.name, "rows 1000..1048 worst", run_case(case, rows=(1000, 1048)))
+    # the int8 path at M = 2048 (a slow kernel at this size); the oracle computes a 256-row window
+    say("gemm", case.name, "rows 900..1156 worst", run_case(case, rows=(900, 1156)))
 
 
 @pytest.mark.parametrize("M", [1, 4, 8])
@@ -877,33 +877,55 @@ def test_matrix_gemm_llama7b_reduced_m256_full_output():
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2])
-def test_matrix_gemm_llama7b_full_size_sampled_rows(idx):
-    """The benchmark's launch configuration: M = 2048, fused quantize+pack, matrix layout."""
+def test_matrix_gemm_llama7b_full_size_whole_output(idx):
+    """The benchmark's launch configuration (M = 2048, fused quantize+pack, matrix layout): every element of
+    the output against the oracle under the plain criterion |err| <= 1e-5 * sum_b |term_b|."""
     case = inputs.llama7b_prefill()[idx]
-    say("matrix gemm", case.name, "rows 1000..1048 worst",
-        run_case(case, rows=(1000, 1048), layout=MAT, fused=True))
+    worst = run_case(case, layout=MAT, fused=True)
+    say("matrix gemm", case.name, "whole output, worst err / sum|terms|", worst)
+    assert worst <= 1e-5
 
 
 @pytest.mark.parametrize("block", [16, 32, 64])
-@pytest.mark.parametrize("spread", ["llm", "adversarial"])
+@pytest.mark.parametrize("spread", ["window", "adversarial"])
 def test_matrix_gemm_all_width_pairs_ragged_shapes(block, spread):
-    """Random mantissas and independent random block exponents (within 8 binades, and over 50 binades):
-    short sums in which a large block whose products cancel can sit next to the block that carries
-    the result.  The matrix-core path is bounded against the size of the individual products there
-    (see check_product); on the LLM-shaped workloads it meets the plain criterion (tests above)."""
+    """Random mantissas and independent random block exponents.  In rows and columns 0..9 about half of the
+    blocks are made to cancel exactly (+qmax, -qmax against two equal weights) while holding the largest
+    products, and the other blocks, which carry the result, sit at the bottom of the exponent range.
+    window: the exponent sums Ea + Eb of an output's blocks span at most 25 - wa - wb binades.  The matrix
+      instruction keeps 24 bits below its largest single product and a product has at most wa + wb - 2 bits, so
+      nothing a smaller block contributed is pushed out: the plain criterion must hold.
+    adversarial: over 50 binades the matrix-core path is bounded against the size of the individual products
+      (see check_product)."""
     rng = np.random.default_rng(400 + block)
     M, N, K = 45, 70, 5 * 64
-    elo, ehi = (120, 128) if spread == "llm" else (100, 150)
+    nb = K // block
     for wa in range(2, 9):
         for wb in range(2, 9):
-            qa, ea = random_operand(rng, M, K, block, wa, elo, ehi)
-            qb, eb = random_operand(rng, N, K, block, wb, elo, ehi)
+            if spread == "window":
+                D = 25 - wa - wb
+                sa = (2 * D + 2) // 3
+                sb = D - sa
+                hia, hib = 128, 122
+            else:
+                sa = sb = 50
+                hia = hib = 150
+            qa, ea = random_operand(rng, M, K, block, wa, hia - sa, hia + 1)
+            qb, eb = random_operand(rng, N, K, block, wb, hib - sb, hib + 1)
+            cancel = rng.random(nb) < 0.5
+            ea[:10], eb[:10] = hia - sa, hib - sb
+            for j in np.nonzero(cancel)[0]:
+                qa[:10, j * block:(j + 1) * block] = 0
+                qa[:10, j * block] = 2 ** (wa - 1) - 1
+                qa[:10, j * block + 1] = -(2 ** (wa - 1) - 1)
+                qb[:10, j * block:j * block + 2] = 2 ** (wb - 1) - 1
+                ea[:10, j], eb[:10, j] = hia, hib
             A, fa = gpu_operand(qa, ea, block, wa, layout=MAT)
             B, fb = gpu_operand(qb, eb, block, wb, layout=MAT)
             y = mx.gemm(A, fa, B, fb, M, N, K, layout=MAT)
             torch.cuda.synchronize()
             y_ref, mag = orc.gemm(qa, ea, wa, qb, eb, wb, block, want_mag=True)
-            me = product_magnitude(qa, ea, wa, qb, eb, wb, block)
+            me = None if spread == "window" else product_magnitude(qa, ea, wa, qb, eb, wb, block)
             check_product(host(y)[0], y_ref, mag, "matrix wa=%d wb=%d block=%d" % (wa, wb, block), me)
     say("matrix layout: all width pairs ok, block", block, spread)
 
