@@ -93,8 +93,8 @@ typedef enum { MX_OK = 0, MX_ERR_BAD_ARG = 1, MX_ERR_UNSUPPORTED = 2, MX_ERR_DEV
  *       can therefore push out low bits that much smaller blocks had contributed.  Guaranteed for any in-range
  *       input:  |err| <= 1e-5 * sum_blocks |block term|  +  1e-6 * sum_k |product_k|.  The first term alone
  *       holds whenever, for an output element, the exponent sums Ea + Eb of its blocks span at most
- *       25 - wa - wb binades (13 for 8-bit by 4-bit operands: a product has at most wa + wb - 2 bits, so
- *       nothing is pushed out then) -- and it
+ *       24 - wa - wb binades (12 for 8-bit by 4-bit operands: a product of mantissa pieces has at most
+ *       wa + wb - 1 bits, so nothing is pushed out then) -- and it
  *       holds on LLM-shaped data (heavy tails, outlier channels), where products do not cancel inside blocks
  *       to that degree.  The weaker bound is still tighter than that of a float product of the dequantized
  *       operands, Section 3.2's emulated operator.  Callers that need the first term alone on arbitrary data

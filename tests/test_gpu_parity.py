@@ -886,15 +886,31 @@ def test_matrix_gemm_llama7b_full_size_whole_output(idx):
     assert worst <= 1e-5
 
 
+@pytest.mark.parametrize("N,wa", [(32 * 256 + 300, 8), (32 * 256 + 128, 4), (64 * 256 + 1, 6)])
+def test_matrix_gemm_more_than_one_round_of_tiles_ragged_n(N, wa):
+    """M = 2048 with N a little over whole rounds of resident workgroups (two workgroups per compute unit, banded
+    tile order, a ragged last column of tiles; one- and two-piece left operands).  Whole output."""
+    rng = np.random.default_rng(N + wa)
+    M, K, block = 2048, 256, 32
+    x = (rng.standard_normal((M, K)) * np.exp2(rng.integers(-3, 4, size=(M, 1)))).astype(np.float32)
+    wt = (rng.standard_normal((N, K)) * 0.02).astype(np.float32)
+    fa, fb = mx.fmt(block, wa), mx.fmt(block, 4)
+    y = mx.gemm(mx.quantize_pack(dev(x), fa, MAT), fa, mx.quantize_pack(dev(wt), fb, MAT), fb, M, N, K, layout=MAT)
+    torch.cuda.synchronize()
+    y_ref, mag = orc.linear(x, wt, block, wa, 4, want_mag=True)
+    say("ragged rounds, N", N, "worst", check_product(host(y)[0], y_ref, mag, "ragged rounds N=%d" % N))
+
+
 @pytest.mark.parametrize("block", [16, 32, 64])
 @pytest.mark.parametrize("spread", ["window", "adversarial"])
 def test_matrix_gemm_all_width_pairs_ragged_shapes(block, spread):
     """Random mantissas and independent random block exponents.  In rows and columns 0..9 about half of the
     blocks are made to cancel exactly (+qmax, -qmax against two equal weights) while holding the largest
     products, and the other blocks, which carry the result, sit at the bottom of the exponent range.
-    window: the exponent sums Ea + Eb of an output's blocks span at most 25 - wa - wb binades.  The matrix
-      instruction keeps 24 bits below its largest single product and a product has at most wa + wb - 2 bits, so
-      nothing a smaller block contributed is pushed out: the plain criterion must hold.
+    window: the exponent sums Ea + Eb of an output's blocks span at most 24 - wa - wb binades.  The matrix
+      instruction keeps 24 bits below its largest single product and a product of two mantissa pieces has at most
+      wa + wb - 1 bits (16h * 16h' can pass the product of the mantissas themselves by a binade), so nothing a
+      smaller block contributed is pushed out: the plain criterion must hold.
     adversarial: over 50 binades the matrix-core path is bounded against the size of the individual products
       (see check_product)."""
     rng = np.random.default_rng(400 + block)
@@ -903,7 +919,7 @@ def test_matrix_gemm_all_width_pairs_ragged_shapes(block, spread):
     for wa in range(2, 9):
         for wb in range(2, 9):
             if spread == "window":
-                D = 25 - wa - wb
+                D = 24 - wa - wb
                 sa = (2 * D + 2) // 3
                 sb = D - sa
                 hia, hib = 128, 122
