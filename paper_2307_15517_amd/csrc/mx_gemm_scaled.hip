@@ -103,8 +103,13 @@ __device__ __forceinline__ void wait_vmcnt() {
 // QO: 0 = fp32 result; 1 / 2 = add the bias and quantize the tile to an output format of one / two
 // mantissa pieces (Section 3.2 of the paper: the emulated operator quantizes its result; Fig. 2b: the
 // linear layer's bias is MXInt too), writing the packed operand the next product reads.
-template <int PA, int PB, int TM, int TN, int S, int OCC, int QO>
-__global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
+// WS: 1 = eight waves, the four extra ones ("copy waves", one per SIMD next to a matrix wave) issue every
+// global -> LDS copy and never touch the matrix cores.  A wave issues in order, so a matrix wave that has to
+// wait for the copy path to take its copy also delays its next matrix instruction; with the copies in waves
+// of their own the matrix waves only ever wait for the barrier.  For launches with one workgroup per compute
+// unit (the second workgroup of the OCC = 2 form plays that part otherwise).
+template <int PA, int PB, int TM, int TN, int S, int OCC, int QO, int WS>
+__global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kernel(ScaledArgs g) {
     constexpr int kStages = S;
     constexpr int UA = (PA == 2) ? 2 * TM : TM;        // units of the A tile per K step
     constexpr int UB = (PB == 2) ? 2 * TN : TN;
@@ -122,7 +127,10 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     constexpr int SCALES = NT * 256;                   // bytes of one scale slot
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];   // kStages stages, then 2 scale slots
 
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int wave8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int wave = wave8 & 3;                        // position among the matrix waves, or among the copy waves
+    const bool copier = WS != 0 && wave8 >= 4;         // a copy wave
+    const bool copies = WS == 0 || copier;             // this wave issues copies
     const int wm = wave >> 1, wn = wave & 1;
     // Workgroup i runs on XCD i % 8, each with its own L2.  Give every XCD one contiguous range of tiles of
     // an order in which consecutive tiles form a compact block of the tile grid (below), so that the tiles
@@ -269,16 +277,20 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     // for the next step, the copies for step ks+3 and the scale traffic are slotted between them so
     // that the matrix pipe never waits for them.
     if (g.ksteps > 0) {
-        issue(0, 0);
+        if (copies) {
+            issue(0, 0);
 #pragma unroll
-        for (int q = 0; q < NSC; ++q) issue_scale_one(q, 0, 0);
+            for (int q = 0; q < NSC; ++q) issue_scale_one(q, 0, 0);
 #pragma unroll
-        for (int st = 1; st < S; ++st) issue(st, st);
-        wait_vmcnt<(S - 1) * NLOAD>();
+            for (int st = 1; st < S; ++st) issue(st, st);
+            wait_vmcnt<(S - 1) * NLOAD>();
+        }
         __syncthreads();
+        if (!copier) {
 #pragma unroll
-        for (int n = 0; n < NUA + NUB; ++n) read_unit(n, 0, std::integral_constant<int, 0>{});
-        read_scales(0, nxA, nxB);
+            for (int n = 0; n < NUA + NUB; ++n) read_unit(n, 0, std::integral_constant<int, 0>{});
+            read_scales(0, nxA, nxB);
+        }
     }
     constexpr int NM = PA * PB * RA * RB;              // MFMAs per K step
     int cur = 0;                                       // stage of the current step: ks % S
@@ -287,6 +299,30 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     const uint32_t last_off = (uint32_t)((g.ksteps - 1) * kUnitBytes);
     uint32_t copy_off = (uint32_t)S * kUnitBytes;
     copy_off = copy_off < last_off ? copy_off : last_off;
+    if (copier) {
+        // the copy waves' loop: the same waits, barriers and copies, in the same order, as the WS = 0 form
+        for (int64_t ks4 = 0; ks4 < groups; ++ks4) {
+            auto cstep = [&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                wait_vmcnt<(S - 2) * NLOAD + (j == 1 ? NSC : 0)>();
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < NI; ++q) copy_item(src[q] + copy_off, lds0 + cur * STAGE + dst[q]);
+                if (j == 0) {
+#pragma unroll
+                    for (int q = 0; q < NSC; ++q) issue_scale_one(q, ks4 + 1, (int)((ks4 + 1) & 1));
+                }
+                cur = cur + 1 == S ? 0 : cur + 1;
+                copy_off = copy_off + kUnitBytes < last_off ? copy_off + kUnitBytes : last_off;
+            };
+            cstep(std::integral_constant<int, 0>{});
+            cstep(std::integral_constant<int, 1>{});
+            cstep(std::integral_constant<int, 2>{});
+            cstep(std::integral_constant<int, 3>{});
+        }
+        wait_vmcnt<0>();                                  // the clamped tail copies must not outlive the LDS
+        return;
+    }
     for (int64_t ks4 = 0; ks4 < groups; ++ks4) {
 #pragma unroll
         for (int t = 0; t < RA; ++t) scA[t] = nxA[t];
@@ -300,19 +336,20 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
             const int nxt = cur + 1 == S ? 0 : cur + 1;
             // side work of this step, in issue order: LDS reads for step ks+1, copies for step ks+S,
             // at j == 0 the scale copies of the next group, at j == 3 the read of those scales
-            constexpr int NAUX = (NUA + NUB) + NI + (j == 0 ? NSC : 0) + (j == 3 ? 1 : 0);
+            constexpr int NCP = WS ? 0 : NI, NSCP = WS ? 0 : NSC;      // copies issued by this wave
+            constexpr int NAUX = (NUA + NUB) + NCP + (j == 0 ? NSCP : 0) + (j == 3 ? 1 : 0);
             auto aux = [&](int x) {
                 if (x < NUA + NUB) { read_unit(x, nxt, std::integral_constant<int, set ^ 1>{}); return; }
                 x -= NUA + NUB;
-                if (x < NI) { copy_item(src[x] + copy_off, lds0 + cur * STAGE + dst[x]); return; }
-                x -= NI;
-                if (j == 0) issue_scale_one(x, ks4 + 1, (int)((ks4 + 1) & 1));
+                if (x < NCP) { copy_item(src[x] + copy_off, lds0 + cur * STAGE + dst[x]); return; }
+                x -= NCP;
+                if (j == 0 && NSCP > 0) issue_scale_one(x, ks4 + 1, (int)((ks4 + 1) & 1));
                 if (j == 3) read_scales((int)((ks4 + 1) & 1), nxA, nxB);
             };
             __builtin_amdgcn_sched_barrier(0);
             // newer than D(ks+1): the data copies of the last S-2 steps, and at j == 1 the scale copies
             // issued at the end of the previous step (at other steps they are simply awaited too)
-            wait_vmcnt<(S - 2) * NLOAD + (j == 1 ? NSC : 0)>();
+            if constexpr (WS == 0) wait_vmcnt<(S - 2) * NLOAD + (j == 1 ? NSC : 0)>();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
             // one piece pair after the other: consecutive MFMAs never share an accumulator
@@ -336,7 +373,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
         kstep(std::integral_constant<int, 2>{});
         kstep(std::integral_constant<int, 3>{});
     }
-    wait_vmcnt<0>();                                      // the clamped tail copies must not outlive the LDS
+    if constexpr (WS == 0) wait_vmcnt<0>();               // the clamped tail copies must not outlive the LDS
 
     const int64_t rtA0 = (bm * 2 + wm) * RA, rtB0 = (bn * 2 + wn) * RB;
     const int i = lane & 31, h = lane >> 5;
@@ -467,14 +504,15 @@ __global__ __launch_bounds__(256, OCC) void gemm_scaled_kernel(ScaledArgs g) {
     }
 }
 
-template <int PA, int PB, int TM, int TN, int S, int OCC, int QO = 0>
+template <int PA, int PB, int TM, int TN, int S, int OCC, int QO = 0, int WS = 0>
 mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
+    static_assert(WS == 0 || (OCC == 1 && QO == 0), "copy waves: one workgroup per compute unit, fp32 result");
     constexpr int UA = (PA == 2) ? 2 * TM : TM, UB = (PB == 2) ? 2 * TN : TN;
     constexpr int pipe = S * (UA + UB) * kUnitBytes + 2 * (2 * TM + 2 * TN) * 256;
     constexpr int turn = QO == 0 ? 0 : 4 * 32 * (32 * TN + 4) * 4 + 64 * TN * 4;     // quantized ending
     constexpr int smem = pipe > turn ? pipe : turn;
     static_assert(smem * OCC <= 160 * 1024, "LDS budget of one compute unit");
-    auto kern = gemm_scaled_kernel<PA, PB, TM, TN, S, OCC, QO>;
+    auto kern = gemm_scaled_kernel<PA, PB, TM, TN, S, OCC, QO, WS>;
     static std::atomic<uint64_t> done{0};
     if (!allow_dynamic_lds((const void*)kern, smem, done)) return MX_ERR_DEVICE;
     const int64_t tiles_m = ceil_div(g.M, 64 * TM), tiles_n = ceil_div(g.N, 64 * TN);
@@ -483,7 +521,7 @@ mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
     g.tiles_m = (int32_t)tiles_m;
     g.tiles_n = (int32_t)tiles_n;
     dim3 grid((unsigned)(ceil_div(tiles_m * tiles_n, 8) * 8), (unsigned)batch);
-    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
+    hipLaunchKernelGGL(kern, grid, dim3(WS ? 512 : 256), smem, st, g);
     MX_HIP_LAUNCH_CHECK();
     return MX_OK;
 }
@@ -492,12 +530,14 @@ mx_status launch_scaled(ScaledArgs& g, int64_t batch, hipStream_t st) {
 // pieces, so the tile is wider along N.  When there are at least two tiles per compute unit and
 // the stages are small enough, two workgroups share a compute unit (three stages each), so that
 // one workgroup's barrier and copy waits hide under the other's MFMAs; otherwise one workgroup
-// per compute unit runs with four stages.
+// per compute unit runs with four copy waves beside its four matrix waves and five stages (the
+// copies of a K step are requested four steps ahead).
 template <int PA, int PB, int QO = 0>
 mx_status pick_tile(ScaledArgs& g, int64_t batch, hipStream_t st) {
     const int64_t tiles = ceil_div(g.M, 128) * ceil_div(g.N, 256) * batch;
     if constexpr (PB == 1) {
         if (tiles >= 2 * 256) return launch_scaled<PA, PB, 2, 4, 3, 2, QO>(g, batch, st);
+        if constexpr (QO == 0) return launch_scaled<PA, PB, 2, 4, 5, 1, 0, 1>(g, batch, st);
         return launch_scaled<PA, PB, 2, 4, 4, 1, QO>(g, batch, st);
     } else {
         static_assert(QO == 0, "the quantized ending is built for one-piece right operands");
