@@ -10,6 +10,8 @@ three linears divided by the wall time of the step (quantizer and pack included)
 Besides the contract fields the JSON line carries
   roofline      the product kernel: algorithmic 2*M*N*K per launch / average launch duration
                 (HIP events around every mx_gemm of the timed region) against the int8 MFMA peak;
+                "achievable": what a bare loop of matrix instructions reaches on this GPU (zeros and random
+                operands, with the shader clock each ran at) and what streaming kernels reach;
   kernels       HBM-bound kernels timed on their own over rings of distinct buffers larger than the
                 last-level cache: the quantizer (GB/s) and the decode linear (LLaMA-13B shapes);
   cpu_baseline  the CPU oracle timed on a bounded sample of the same workload.
@@ -26,6 +28,100 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 INT8_MFMA_PEAK_TOPS = 5000.0
+MIN_LAUNCHES = 200            # launches behind every per-kernel figure
+
+
+class Probes:
+    """ctypes front end of libmx_probes.so (csrc/probes/mx_probes.hip): bare streaming kernels and bare loops of
+    matrix instructions, the denominators a kernel can be held against on this GPU besides the published peaks."""
+
+    def __init__(self, torch, dev):
+        import ctypes
+        path = os.path.join(ROOT, "paper_2307_15517_amd", "libmx_probes.so")
+        if not os.path.exists(path):
+            raise FileNotFoundError("%s is missing: build it with `python -m paper_2307_15517_amd.build`" % path)
+        self.lib = ctypes.CDLL(path)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        self.lib.mxp_read.argtypes = [vp, sz, vp, vp]
+        self.lib.mxp_write.argtypes = [vp, sz, vp]
+        self.lib.mxp_copy.argtypes = [vp, vp, sz, vp]
+        self.lib.mxp_mfma_fp6.argtypes = [vp, vp, i32, vp, vp, vp]
+        self.lib.mxp_mfma_i8.argtypes = [vp, vp, i32, vp, vp, vp]
+        self.lib.mxp_mfma_waves.restype = i32
+        self.torch, self.dev, self.ctypes = torch, dev, ctypes
+        self.stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        self.sink = torch.zeros(16, dtype=torch.float32, device=dev)
+        self.pool = None
+        self._floors = {}
+
+    def _pool(self):
+        if self.pool is None:           # 1.5 GB touched once: rings of distinct buffers are slices of it
+            self.pool = self.torch.ones(1536 << 20, dtype=self.torch.uint8, device=self.dev)
+        return self.pool
+
+    def stream_ms(self, kind, nbytes, timer):
+        """Median time of one streaming pass (read / write / copy of nbytes) over a ring of distinct buffers
+        larger than the last-level cache."""
+        key = (kind, int(nbytes))
+        if key in self._floors:
+            return self._floors[key]
+        nbytes = int(nbytes) // 256 * 256
+        pool = self._pool()
+        span = nbytes * (2 if kind == "copy" else 1)
+        if span > pool.numel():
+            raise ValueError("stream probe of %d bytes does not fit the %d-byte pool" % (span, pool.numel()))
+        nring = max(1, min(64, int(min(1.3e9, pool.numel()) // span)))     # every buffer of the ring lies inside the pool
+        assert nring * span <= pool.numel()
+        base = pool.data_ptr()
+        vp = self.ctypes.c_void_p
+        calls = []
+        for r in range(nring):
+            a = base + r * span
+            if kind == "read":
+                calls.append((self.lib.mxp_read, (vp(a), nbytes, vp(self.sink.data_ptr()), self.stream)))
+            elif kind == "write":
+                calls.append((self.lib.mxp_write, (vp(a), nbytes, self.stream)))
+            else:
+                calls.append((self.lib.mxp_copy, (vp(a + nbytes), vp(a), nbytes, self.stream)))
+
+        def fn(i):
+            f, a = calls[i % nring]
+            assert f(*a) == 0
+        ms = timer(fn, 2 * nring)
+        self._floors[key] = ms
+        return ms
+
+    def mfma(self, kind, pattern, iters=20000):
+        """TOP/s and shader clock of a bare loop of matrix instructions: kind "fp6" (block-scaled 6-bit floats,
+        32x32x64) or "i8" (32x32x32), operands all zero or random bits."""
+        torch = self.torch
+        ndw = 64 * 4 * (8 if kind == "fp6" else 4)
+        if pattern == "zeros":
+            a = torch.zeros(ndw, dtype=torch.int32, device=self.dev)
+            b = torch.zeros(ndw, dtype=torch.int32, device=self.dev)
+        else:
+            g = torch.Generator(device=self.dev)
+            g.manual_seed(7)
+            a = torch.randint(-2 ** 31, 2 ** 31 - 1, (ndw,), dtype=torch.int32, device=self.dev, generator=g)
+            b = torch.randint(-2 ** 31, 2 ** 31 - 1, (ndw,), dtype=torch.int32, device=self.dev, generator=g)
+        waves = self.lib.mxp_mfma_waves()
+        out = torch.zeros((waves, 2), dtype=torch.int64, device=self.dev)
+        fn = self.lib.mxp_mfma_fp6 if kind == "fp6" else self.lib.mxp_mfma_i8
+        vp = self.ctypes.c_void_p
+        args = (vp(a.data_ptr()), vp(b.data_ptr()), iters, vp(out.data_ptr()), vp(self.sink.data_ptr()), self.stream)
+        assert fn(*args) == 0                                   # warm-up
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            assert fn(*args) == 0
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        ops = waves * iters * 16 * 2.0 * 32 * 32 * (64 if kind == "fp6" else 32)
+        o = out.cpu().numpy().astype("float64")
+        ghz = float(__import__("numpy").median(o[:, 0] / o[:, 1])) * 0.1          # cycles per 10 ns tick
+        return {"TOPS": round(ops / ms / 1e9, 1), "shader_clock_GHz": round(ghz, 3)}
 
 
 def recorded_traffic():
@@ -154,44 +250,72 @@ def main():
                 "traffic": recorded_traffic() if args.layout == "matrix" else None,
                 "avg_launch_ms": round(gemm_ms / len(gemm_events), 4)}
 
+    def time_launches(fn, n):
+        """Median over batches of the mean time per launch: batches of n back-to-back launches between two
+        events, at least MIN_LAUNCHES launches in all (never fewer than 5 batches)."""
+        batches = max(5, -(-MIN_LAUNCHES // n))
+        ms = []
+        for _ in range(batches):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(n):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1) / n)
+        return float(np.median(ms))
+
+    # what the bare matrix pipe and bare streaming kernels reach on this GPU (the achievable denominators)
+    probes = Probes(torch, dev)
+    if not args.no_kernels:
+        fp6z, fp6r = probes.mfma("fp6", "zeros"), probes.mfma("fp6", "random")
+        i8z, i8r = probes.mfma("i8", "zeros"), probes.mfma("i8", "random")
+        big = 1 << 30
+        # the product takes two 6-bit instructions per int8-equivalent instruction (8-bit activations = two pieces)
+        eq = fp6r["TOPS"] / 2
+        roofline["achievable"] = {
+            "mfma_fp6_loop_zeros": fp6z, "mfma_fp6_loop_random": fp6r,
+            "mfma_i8_loop_zeros": i8z, "mfma_i8_loop_random": i8r,
+            "int8_equivalent_TOPS_of_two_piece_fp6_random": round(eq, 1),
+            "frac_of_achievable": round(achieved / eq, 4),
+            "stream_read_1GiB_GBps": round(big / probes.stream_ms("read", big, time_launches) / 1e6, 1),
+            "stream_write_1GiB_GBps": round(big / probes.stream_ms("write", big, time_launches) / 1e6, 1),
+            "stream_copy_512MiB_GBps": round(big / probes.stream_ms("copy", big // 2, time_launches) / 1e6, 1)}
+
+    def with_floor(entry, nbytes, ms):
+        """Adds the time a bare streaming read of the same number of bytes takes on this GPU, and the kernel's
+        time as a fraction of it (a read is the fastest way to touch that many bytes)."""
+        floor = probes.stream_ms("read", nbytes, time_launches)
+        entry["read_floor_us"] = round(floor * 1e3, 2)
+        entry["frac_of_read_floor"] = round(floor / ms, 4)
+        return entry
+
     # ---------------------------------------------------------------- HBM-bound kernels on their own
     kernels = {}
     if not args.no_kernels:
-        def time_launches(fn, n, reps=3):
-            best = None
-            for _ in range(reps):
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(n):
-                    fn(i)
-                e1.record()
-                torch.cuda.synchronize()
-                ms = e0.elapsed_time(e1) / n
-                best = ms if best is None else min(best, ms)
-            return best
-
         # quantizer: 4 bytes read + w/8 + 1/block bytes written per element, over a ring of distinct inputs
         # (> 1 GB in all) so that nothing is served from the last-level cache
         for w in (work[0], work[2]):
             c = w["case"]
             nring = int(1.3e9 // (c.M * c.K * 4)) + 1
             qring = [torch.randn((c.M, c.K), dtype=torch.float32, device=dev) for _ in range(nring)]
-            ms = time_launches(lambda i: mx.mx_quantize(qring[i % nring], 1, c.M, c.K, c.K, 0, 1, w["fa"],
-                                                        w["mant"], w["exps"]), 2 * nring)
+            # pre-marshalled calls: per-call marshalling in Python would cost as much as these kernels run
+            qcalls = [mx.bound("mx_quantize", q, 1, c.M, c.K, c.K, 0, 1, w["fa"], w["mant"], w["exps"]) for q in qring]
+            ms = time_launches(lambda i: qcalls[i % nring](), 2 * nring)
             qbytes = c.M * c.K * (4 + c.wx / 8 + 1 / c.block)
-            kernels["quantize_%dx%d_w%d_b%d" % (c.M, c.K, c.wx, c.block)] = {
+            kernels["quantize_%dx%d_w%d_b%d" % (c.M, c.K, c.wx, c.block)] = with_floor({
                 "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
+                "us": round(ms * 1e3, 2), "bytes": int(qbytes)}, qbytes, ms)
             if c.K == 11008:
                 # the paper's own block shape: 16 columns x 2 rows per exponent, MXInt((16,2),8,7)
                 f2 = mx.fmt(16, 8, block_rows=2)
                 e2 = torch.empty(mx.mx_exps_bytes(1, c.M, c.K, f2), dtype=torch.uint8, device=dev)
-                ms = time_launches(lambda i: mx.mx_quantize(qring[i % nring], 1, c.M, c.K, c.K, 0, 1, f2,
-                                                            w["mant"], e2), 2 * nring)
-                kernels["quantize_%dx%d_w8_b16x2" % (c.M, c.K)] = {
+                qcalls = [mx.bound("mx_quantize", q, 1, c.M, c.K, c.K, 0, 1, f2, w["mant"], e2) for q in qring]
+                ms = time_launches(lambda i: qcalls[i % nring](), 2 * nring)
+                kernels["quantize_%dx%d_w8_b16x2" % (c.M, c.K)] = with_floor({
                     "GBps": round(qbytes / ms / 1e6, 1), "frac_hbm": round(qbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                    "us": round(ms * 1e3, 2), "bytes": int(qbytes)}
+                    "us": round(ms * 1e3, 2), "bytes": int(qbytes)}, qbytes, ms)
             if c.K == 11008:
                 # the paper's other block formats at the same shape: Block Minifloat (1 + 4 + 3 bits) and Block
                 # Logarithm (1 + 7 bits), one byte per element + one shared byte per block
@@ -199,19 +323,19 @@ def main():
                 mshared = torch.empty(c.M * c.K // c.block, dtype=torch.uint8, device=dev)
                 for name, fm in (("bmf_e4m3", mx.mx_minifloat_format(c.block, 4, 3, mx.MX_RNE)),
                                  ("bl_e7", mx.mx_minifloat_format(c.block, 7, 0, mx.MX_RNE))):
-                    ms = time_launches(lambda i: mx.mx_quantize_minifloat(qring[i % nring], 1, c.M, c.K, c.K, 0, fm,
-                                                                          mcodes, mshared), 2 * nring)
+                    qcalls = [mx.bound("mx_quantize_minifloat", q, 1, c.M, c.K, c.K, 0, fm, mcodes, mshared) for q in qring]
+                    ms = time_launches(lambda i: qcalls[i % nring](), 2 * nring)
                     mbytes = c.M * c.K * (4 + 1 + 1 / c.block)
-                    kernels["quantize_%s_%dx%d_b%d" % (name, c.M, c.K, c.block)] = {
+                    kernels["quantize_%s_%dx%d_b%d" % (name, c.M, c.K, c.block)] = with_floor({
                         "GBps": round(mbytes / ms / 1e6, 1), "frac_hbm": round(mbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                        "us": round(ms * 1e3, 2), "bytes": int(mbytes)}
+                        "us": round(ms * 1e3, 2), "bytes": int(mbytes)}, mbytes, ms)
             if args.layout == "matrix":
-                ms = time_launches(lambda i: mx.mx_quantize_pack(qring[i % nring], 1, c.M, c.K, c.K, 0, w["fa"], L,
-                                                                 w["A"]), 2 * nring)
+                qcalls = [mx.bound("mx_quantize_pack", q, 1, c.M, c.K, c.K, 0, w["fa"], L, w["A"]) for q in qring]
+                ms = time_launches(lambda i: qcalls[i % nring](), 2 * nring)
                 pbytes = c.M * c.K * 4 + mx.mx_packed_bytes(1, c.M, c.K, w["fa"], L)
-                kernels["quantize_pack_matrix_%dx%d_w%d_b%d" % (c.M, c.K, c.wx, c.block)] = {
+                kernels["quantize_pack_matrix_%dx%d_w%d_b%d" % (c.M, c.K, c.wx, c.block)] = with_floor({
                     "GBps": round(pbytes / ms / 1e6, 1), "frac_hbm": round(pbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                    "us": round(ms * 1e3, 2), "bytes": int(pbytes)}
+                    "us": round(ms * 1e3, 2), "bytes": int(pbytes)}, pbytes, ms)
             del qring
         # width cast inside the format, 8 -> 4 bits at the prefill activation shape:
         # (8 + 4)/8 + 2/block bytes per element
@@ -225,9 +349,9 @@ def main():
         calls = [mx.bound("mx_cast", m, e8, 1, c.M, c.K, work[2]["fa"], f4, m4, e4) for m in m8s]
         ms = time_launches(lambda i: calls[i % nring](), 2 * nring)
         cbytes = c.M * c.K * (1.5 + 2 / c.block)
-        kernels["cast_%dx%d_w8_to_w4_b%d" % (c.M, c.K, c.block)] = {
+        kernels["cast_%dx%d_w8_to_w4_b%d" % (c.M, c.K, c.block)] = with_floor({
             "GBps": round(cbytes / ms / 1e6, 1), "frac_hbm": round(cbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-            "us": round(ms * 1e3, 2), "bytes": int(cbytes)}
+            "us": round(ms * 1e3, 2), "bytes": int(cbytes)}, cbytes, ms)
         del m8s, calls
         # the whole emulated linear layer (product + MXInt bias + output quantizer) in one kernel, against the
         # product followed by a separate quantize+pack of its fp32 result; 8-bit activations in and out, 4-bit
@@ -269,9 +393,9 @@ def main():
                 calls = [mx.bound("mx_linear", xd, M, dc.K, dc.K, fa, scratch, Bw, dc.N, fb, LF, y, dc.N) for Bw in Bs]
                 ms = time_launches(lambda i: calls[i % nring](), 2 * nring)
                 nbytes = 0.5625 * dc.N * dc.K + 4 * M * dc.K + 4 * M * dc.N
-                kernels["linear_%s_M%d" % (dc.name, M)] = {
+                kernels["linear_%s_M%d" % (dc.name, M)] = with_floor({
                     "GBps": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                    "us": round(ms * 1e3, 2), "bytes": int(nbytes)}
+                    "us": round(ms * 1e3, 2), "bytes": int(nbytes)}, nbytes, ms)
                 del Bs, B0, wd, bm, be
 
         # mixed-precision attention, 32 heads x 2048 positions x 128: both products are bound by the fp32
@@ -299,8 +423,8 @@ def main():
         dens = lambda f_: f_.mant_bits / 8 + 1 / f_.block
 
         def attn_entry(name, ms, nbytes, ops=None):
-            e = {"GBps": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                 "us": round(ms * 1e3, 2), "bytes": int(nbytes)}
+            e = with_floor({"GBps": round(nbytes / ms / 1e6, 1), "frac_hbm": round(nbytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                            "us": round(ms * 1e3, 2), "bytes": int(nbytes)}, nbytes, ms)
             if ops:
                 e["TOPS"] = round(ops / ms / 1e9, 1)
             kernels["attention_w%d%d%d%d_%s" % (wq, wk, wp, wv, name)] = e

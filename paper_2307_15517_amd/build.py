@@ -17,6 +17,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmx.so")
+PROBES_SRC = os.path.join(CSRC, "probes", "mx_probes.hip")
+PROBES_LIB = os.path.join(HERE, "libmx_probes.so")      # roofline probes of the benchmark, not part of libmx
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -70,6 +72,14 @@ def build(verbose: bool = True, jobs: int = 8) -> str:
     os.replace(tmp, LIB)
     if verbose:
         print("linked", os.path.relpath(LIB, ROOT), flush=True)
+    tmp = PROBES_LIB + ".tmp.%d" % os.getpid()
+    p = subprocess.run([HIPCC] + FLAGS + ["-shared", PROBES_SRC, "-o", tmp], stdout=subprocess.PIPE,
+                       stderr=subprocess.STDOUT, text=True)
+    if p.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s" % (PROBES_SRC, p.stdout))
+    os.replace(tmp, PROBES_LIB)
+    if verbose:
+        print("linked", os.path.relpath(PROBES_LIB, ROOT), flush=True)
     return LIB
 
 

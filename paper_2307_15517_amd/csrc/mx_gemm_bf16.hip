@@ -298,7 +298,8 @@ __global__ __launch_bounds__(256, OCC) void gemm_bf16_kernel(BfArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = (rtA0 + ta) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (m < g.M && n < g.N) Y[m * g.ldy + n] = acc[ta][tb][r];
+                // written once and not read again by this kernel: a streaming store keeps the operands in the L2
+                if (m < g.M && n < g.N) __builtin_nontemporal_store(acc[ta][tb][r], &Y[m * g.ldy + n]);
             }
         }
     }

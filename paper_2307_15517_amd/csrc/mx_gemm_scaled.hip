@@ -498,7 +498,8 @@ __global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kern
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t m = (rtA0 + ta) * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (m < g.M && n < g.N) Y[m * g.ldy + n] = __builtin_ldexpf(acc[ta][tb][r], g.eadj);
+                // written once and not read again by this kernel: a streaming store keeps the operands in the L2
+                if (m < g.M && n < g.N) __builtin_nontemporal_store(__builtin_ldexpf(acc[ta][tb][r], g.eadj), &Y[m * g.ldy + n]);
             }
         }
     }
