@@ -31,6 +31,44 @@ INT8_MFMA_PEAK_TOPS = 5000.0
 MIN_LAUNCHES = 200            # launches behind every per-kernel figure
 
 
+class HipEvents:
+    """HIP events created without the system-scope fence (hipEventDisableSystemFence): recording one then costs the
+    stream a marker, not a flush of the caches towards the host, so a pair brackets the kernel between them and little
+    else.  Recorded on the stream the kernels are launched on."""
+    DISABLE_SYSTEM_FENCE = 0x20000000
+
+    def __init__(self, n, stream_handle):
+        import ctypes
+        self.ct = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.stream = ctypes.c_void_p(stream_handle)
+        self.events = []
+        for _ in range(n):
+            e = ctypes.c_void_p()
+            if self.hip.hipEventCreateWithFlags(ctypes.byref(e), self.DISABLE_SYSTEM_FENCE) != 0:
+                raise RuntimeError("hipEventCreateWithFlags failed")
+            self.events.append(e)
+
+    def record(self, i):
+        if self.hip.hipEventRecord(self.events[i], self.stream) != 0:
+            raise RuntimeError("hipEventRecord failed")
+
+    def elapsed_ms(self, i, j):
+        ms = self.ct.c_float()
+        if self.hip.hipEventElapsedTime(self.ct.byref(ms), self.events[i], self.events[j]) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)
+
+    def destroy(self):
+        for e in self.events:
+            self.hip.hipEventDestroy(e)
+        self.events = []
+
+
 class Probes:
     """ctypes front end of libmx_probes.so (csrc/probes/mx_probes.hip): bare streaming kernels and bare loops of
     matrix instructions, the denominators a kernel can be held against on this GPU besides the published peaks."""
@@ -155,6 +193,8 @@ def parse():
     ap.add_argument("--layout", choices=["matrix", "fragment"], default="matrix",
                     help="operand layout of the prefill product: block-scaled matrix cores (default) or int8 MFMA")
     ap.add_argument("--unfused", action="store_true", help="mx_quantize + mx_pack instead of mx_quantize_pack")
+    ap.add_argument("--min-launches", type=int, default=MIN_LAUNCHES,
+                    help="launches behind every per-kernel figure (lower it for counter-collection runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -202,24 +242,29 @@ def main():
         work.append(w)
     total_ops = sum(w["ops"] for w in work)
     gemm_events = []
+    # every call of the step marshalled once, every event created before the clock starts: the host then only
+    # issues, and the gaps between kernels are the GPU's own
+    for w in work:
+        c = w["case"]
+        if args.unfused:
+            w["q_calls"] = [(mx.bound("mx_quantize", x, 1, c.M, c.K, c.K, 0, 1, w["fa"], w["mant"], w["exps"]),
+                             mx.bound("mx_pack", w["mant"], w["exps"], 1, c.M, c.K, w["fa"], L, w["A"])) for x in w["xs"]]
+        else:
+            w["q_calls"] = [(mx.bound("mx_quantize_pack", x, 1, c.M, c.K, c.K, 0, w["fa"], L, w["A"]),) for x in w["xs"]]
+        w["g_calls"] = [mx.bound("mx_gemm", 1, c.M, c.N, c.K, w["A"], w["fa"], w["B"], w["fb"], L, y, c.N, 0) for y in w["Y"]]
+    hip_events = HipEvents(2 * len(work) * args.steps, torch.cuda.current_stream().cuda_stream)
 
     def step(i, timed):
-        for w in work:
-            c = w["case"]
-            x = w["xs"][i % ring]
-            if args.unfused:
-                mx.mx_quantize(x, 1, c.M, c.K, c.K, 0, 1, w["fa"], w["mant"], w["exps"])
-                mx.mx_pack(w["mant"], w["exps"], 1, c.M, c.K, w["fa"], L, w["A"])
-            else:
-                mx.mx_quantize_pack(x, 1, c.M, c.K, c.K, 0, w["fa"], L, w["A"])
+        for wi, w in enumerate(work):
+            for call in w["q_calls"][i % ring]:
+                call()
             if timed:
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
-            mx.mx_gemm(1, c.M, c.N, c.K, w["A"], w["fa"], w["B"], w["fb"], L, w["Y"][i % 2], c.N, 0)
+                e0 = 2 * (i * len(work) + wi)
+                hip_events.record(e0)
+            w["g_calls"][i % 2]()
             if timed:
-                e1.record()
-                gemm_events.append((e0, e1, w["ops"]))
+                hip_events.record(e0 + 1)
+                gemm_events.append((e0, e0 + 1, w["ops"]))
 
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
@@ -239,7 +284,8 @@ def main():
     ms_per_step = 1e3 * sec / args.steps
     value = total_ops * args.steps / sec / 1e12
 
-    gemm_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in gemm_events)
+    gemm_ms = sum(hip_events.elapsed_ms(e0, e1) for e0, e1, _ in gemm_events)
+    hip_events.destroy()
     gemm_ops = sum(o for _, _, o in gemm_events)
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
     kname = ("mx_gemm (block-scaled fp6 MFMA, two mantissa pieces for 8-bit activations)" if args.layout == "matrix"
@@ -253,7 +299,9 @@ def main():
     def time_launches(fn, n):
         """Median over batches of the mean time per launch: batches of n back-to-back launches between two
         events, at least MIN_LAUNCHES launches in all (never fewer than 5 batches)."""
-        batches = max(5, -(-MIN_LAUNCHES // n))
+        if args.min_launches < MIN_LAUNCHES:          # counter-collection runs: a handful of launches per kernel
+            n = max(1, min(n, args.min_launches))
+        batches = max(5, -(-args.min_launches // n)) if args.min_launches >= MIN_LAUNCHES else 1
         ms = []
         for _ in range(batches):
             e0 = torch.cuda.Event(enable_timing=True)

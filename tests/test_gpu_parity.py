@@ -1516,8 +1516,9 @@ def test_quantize_pack_axis0_workload_and_rejections():
 # The entry points allocate nothing and touch only the caller's stream: a graph can capture them
 # ----------------------------------------------------------------------------------------------
 def test_calls_captured_in_a_graph_replay_the_same_bits():
-    """A decode step (three mx_linear calls), a prefill product and an attention call captured into one
-    graph; every replay, with eager work and synchronisation in between, gives the eager bits."""
+    """A decode step (mx_linear at one row, and at four rows through both of its entry points: K slices, arrival
+    counters that every launch leaves at zero), a prefill product and an attention call captured into one graph;
+    every replay, with eager work and synchronisation in between, gives the eager bits."""
     cases = inputs.llama13b_decode(1)[:2]
     work = []
     for c in cases:
@@ -1536,10 +1537,17 @@ def test_calls_captured_in_a_graph_replay_the_same_bits():
     Qp, Kp = (torch.zeros(mx.mx_packed_bytes(2, 96, 64, f16, MAT), dtype=torch.uint8, device=DEV) for _ in range(2))
     Vp = torch.zeros(mx.mx_packed_bytes(2, 64, 96, f16, MAT), dtype=torch.uint8, device=DEV)
     O = torch.zeros((2, 96, 64), dtype=torch.float32, device=DEV)
+    c4 = inputs.llama13b_decode(4)[0]
+    x4 = dev(inputs.make(c4)[0])
+    fa4, fb4 = mx.fmt(c4.block, c4.wx), mx.fmt(c4.block, c4.ww)
+    ws4 = mx.linear_workspace(4, c4.K, c4.N, fa4, fb4, DEV)
+    Y4a, Y4b = (torch.zeros((4, c4.N), dtype=torch.float32, device=DEV) for _ in range(2))
 
     def step():
         for xd, c, fa, scratch, B, fb, y in work:
             mx.mx_linear(xd, 1, c.K, c.K, fa, scratch, B, c.N, fb, mx.MX_LAYOUT_FRAGMENT, y, c.N)
+        mx.mx_linear(x4, 4, c4.K, c4.K, fa4, ws4, work[0][4], c4.N, fb4, mx.MX_LAYOUT_FRAGMENT, Y4a, c4.N)
+        mx.mx_linear_static_workspace(x4, 4, c4.K, c4.K, fa4, work[0][4], c4.N, fb4, mx.MX_LAYOUT_FRAGMENT, Y4b, c4.N)
         mx.mx_quantize_pack(X, 1, 256, 512, 512, 0, f8, MAT, A)
         mx.mx_gemm(1, 256, 384, 512, A, f8, W, f4, MAT, Y, 384, 256 * 384)
         mx.mx_quantize_pack(Q, 2, 96, 64, 64, 96 * 64, f16, MAT, Qp)
@@ -1547,7 +1555,7 @@ def test_calls_captured_in_a_graph_replay_the_same_bits():
         mx.mx_quantize_pack_axis0(V, 2, 96, 64, 64, 96 * 64, f16, MAT, Vp)
         mx.mx_attention(2, 96, 96, 64, Qp, f16, Kp, f16, Vp, f16, f16, 0.125, MAT, O, 64, 96 * 64)
 
-    outs = [w[-1] for w in work] + [Y, O]
+    outs = [w[-1] for w in work] + [Y, O, Y4a, Y4b]
     step()
     torch.cuda.synchronize()
     want = [o.clone() for o in outs]
