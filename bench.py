@@ -8,8 +8,10 @@ are seeded synthetic tensors already resident in HBM.  The step's value is 2*M*N
 three linears divided by the wall time of the step (quantizer and pack included).
 
 Besides the contract fields the JSON line carries
-  roofline      the product kernel: algorithmic 2*M*N*K per launch / average launch duration
-                (HIP events around every mx_gemm of the timed region) against the int8 MFMA peak;
+  roofline      the product kernel: algorithmic 2*M*N*K per launch / average launch duration against the int8
+                MFMA peak; the durations come from a second run of the same K steps with a HIP event on either
+                side of every mx_gemm (the timed steps themselves carry no events: each one stalls the stream
+                for a few microseconds);
                 "achievable": what a bare loop of matrix instructions reaches on this GPU (zeros and random
                 operands, with the shader clock each ran at) and what streaming kernels reach;
   kernels       HBM-bound kernels timed on their own over rings of distinct buffers larger than the
@@ -186,8 +188,10 @@ def recorded_traffic():
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # a step takes about 0.27 ms: a few hundred of them, so that starting and draining the stream (about half a
+    # millisecond between the two host clock readings) does not weigh on the figure
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the separate quantizer / decode timings")
     ap.add_argument("--layout", choices=["matrix", "fragment"], default="matrix",
@@ -254,17 +258,17 @@ def main():
         w["g_calls"] = [mx.bound("mx_gemm", 1, c.M, c.N, c.K, w["A"], w["fa"], w["B"], w["fb"], L, y, c.N, 0) for y in w["Y"]]
     hip_events = HipEvents(2 * len(work) * args.steps, torch.cuda.current_stream().cuda_stream)
 
-    def step(i, timed):
+    def step(i, events):
         for wi, w in enumerate(work):
             for call in w["q_calls"][i % ring]:
                 call()
-            if timed:
+            if events:
                 e0 = 2 * (i * len(work) + wi)
                 hip_events.record(e0)
             w["g_calls"][i % 2]()
-            if timed:
+            if events:
                 hip_events.record(e0 + 1)
-                gemm_events.append((e0, e0 + 1, w["ops"]))
+                gemm_events.append((e0, e0 + 1, wi))
 
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
@@ -274,19 +278,36 @@ def main():
         del src, dst
     for i in range(args.warmup):
         step(i, False)
+    # the timed region: K steps, nothing but the library's launches on the stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, True)
+        step(i, False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec = t1 - t0
     ms_per_step = 1e3 * sec / args.steps
     value = total_ops * args.steps / sec / 1e12
 
+    # the same K steps again with a HIP event on either side of every mx_gemm: the product's launch durations
+    # inside the step (each event costs the stream a few microseconds, which is why the region above has none)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    ms_per_step_events = 1e3 * (time.perf_counter() - t0) / args.steps
+
+    per_shape = []
+    for wi, w in enumerate(work):
+        ms = [hip_events.elapsed_ms(e0, e1) for e0, e1, k in gemm_events if k == wi]
+        c = w["case"]
+        per_shape.append({"shape": "%dx%dx%d" % (c.M, c.N, c.K), "launches": len(ms),
+                          "avg_launch_us": round(1e3 * sum(ms) / len(ms), 2),
+                          "TOPS": round(w["ops"] / (sum(ms) / len(ms) * 1e-3) / 1e12, 1)})
     gemm_ms = sum(hip_events.elapsed_ms(e0, e1) for e0, e1, _ in gemm_events)
     hip_events.destroy()
-    gemm_ops = sum(o for _, _, o in gemm_events)
+    gemm_ops = sum(work[k]["ops"] for _, _, k in gemm_events)
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
     kname = ("mx_gemm (block-scaled fp6 MFMA, two mantissa pieces for 8-bit activations)" if args.layout == "matrix"
              else "mx_gemm (int8 MFMA, block-exponent epilogue)")
@@ -294,7 +315,9 @@ def main():
                 "achieved": round(achieved, 2), "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                 "frac": round(achieved / INT8_MFMA_PEAK_TOPS, 4),
                 "traffic": recorded_traffic() if args.layout == "matrix" else None,
-                "avg_launch_ms": round(gemm_ms / len(gemm_events), 4)}
+                "avg_launch_ms": round(gemm_ms / len(gemm_events), 4),
+                "per_shape": per_shape,
+                "ms_per_step_with_events": round(ms_per_step_events, 4)}
 
     def time_launches(fn, n):
         """Median over batches of the mean time per launch: batches of n back-to-back launches between two
@@ -342,6 +365,22 @@ def main():
     # ---------------------------------------------------------------- HBM-bound kernels on their own
     kernels = {}
     if not args.no_kernels:
+        # the product on its own, back to back on one set of buffers (the operands then stay in the last-level
+        # cache between launches, unlike inside a step), and the same on all-zero operands: the instruction
+        # stream and its cycle count are the same, but zero operands leave the shader clock where it idles,
+        # so the pair tells how much of the product's time is the clock that its operand bits cost
+        if args.layout == "matrix":
+            for w in work:
+                c = w["case"]
+                tag = "gemm_%dx%dx%d" % (c.M, c.N, c.K)
+                zA, zB = torch.zeros_like(w["A"]), torch.zeros_like(w["B"])
+                zero = mx.bound("mx_gemm", 1, c.M, c.N, c.K, zA, w["fa"], zB, w["fb"], L, w["Y"][0], c.N, 0)
+                for name, call in (("back_to_back", w["g_calls"][0]), ("zero_operands", zero)):
+                    ms = time_launches(lambda i: call(), 25)
+                    kernels["%s_%s" % (tag, name)] = {
+                        "us": round(ms * 1e3, 2), "TOPS": round(w["ops"] / ms / 1e9, 1),
+                        "frac_int8_peak": round(w["ops"] / ms / 1e9 / INT8_MFMA_PEAK_TOPS, 4)}
+                del zA, zB
         # quantizer: 4 bytes read + w/8 + 1/block bytes written per element, over a ring of distinct inputs
         # (> 1 GB in all) so that nothing is served from the last-level cache
         for w in (work[0], work[2]):

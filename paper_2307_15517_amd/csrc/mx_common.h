@@ -66,6 +66,16 @@ __host__ __device__ inline FragGeom frag_geom(int64_t rows, int64_t cols, int bl
         if (e__ != hipSuccess) return MX_ERR_DEVICE;           \
     } while (0)
 
+// 16 bytes of an fp32 input tensor that its kernel reads exactly once: a streaming load, so that the tensor does not
+// displace what later calls read again (packed weights stay in the last-level cache from one call to the next).
+// Used where it was measured to pay (the quantize+pack of the prefill path); the plain quantizers run about a tenth
+// slower with it on large inputs and keep ordinary loads.
+typedef float f4v_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 load_once4(const float* p) {
+    const f4v_t t = __builtin_nontemporal_load(reinterpret_cast<const f4v_t*>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
 // ---- device bit helpers ------------------------------------------------------------------------
 // Sign-extended w-bit field at bit offset `bit` of a little-endian stream held in dwords.
 template <int W>

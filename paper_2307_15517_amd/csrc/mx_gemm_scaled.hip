@@ -22,6 +22,16 @@
 #include "mx_gemm.h"
 #include "mx_matrix.h"
 
+// From this many output tiles on, the product runs two workgroups per compute unit (three LDS stages each) instead of
+// one workgroup with copy waves (five stages).
+#ifndef MX_SCALED_TWO_PER_CU_TILES
+#define MX_SCALED_TWO_PER_CU_TILES 512
+#endif
+// Matrix instructions at the end of a K step with no LDS read or copy issued between them.
+#ifndef MX_SCALED_TAIL_MFMAS
+#define MX_SCALED_TAIL_MFMAS 4
+#endif
+
 namespace mx {
 namespace {
 
@@ -111,6 +121,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int PA, int PB, int TM, int TN, int S, int OCC, int QO, int WS>
 __global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kernel(ScaledArgs g) {
     constexpr int kStages = S;
+    static_assert(S >= 3 && S <= 5, "the scale copies of a group must have landed by its step 3");
     constexpr int UA = (PA == 2) ? 2 * TM : TM;        // units of the A tile per K step
     constexpr int UB = (PB == 2) ? 2 * TN : TN;
     constexpr int NU = UA + UB;
@@ -269,8 +280,11 @@ __global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kern
     };
 
     // Pipeline.  Queue of copies, oldest first, when step ks starts:  D(ks+1) ... D(ks+S-1), with
-    // the scale copies of a group right behind the data copies of its step 0.  Waiting until only
-    // the newest S-2 steps' copies are outstanding means D(ks+1) has landed; the barrier then
+    // the scale copies of the next group right ahead of the data copies issued at step 0 of a group.
+    // Copies land in issue order, so once only the data copies of the newest S-2 steps are outstanding
+    // (at step 3 of the group: those issued at steps 0, 1, 2 when S = 5) the scale copies have landed
+    // too, and step 3 may read them; with more than five stages they could still be in flight there.
+    // Waiting until only the newest S-2 steps' copies are outstanding means D(ks+1) has landed; the barrier then
     // publishes it and tells that every wave is done reading the stage of step ks (read into
     // registers during step ks-1), which the copy of step ks+S overwrites.
     // Inside a step the MFMAs (operands already in registers) are issued at once, and the LDS reads
@@ -306,12 +320,12 @@ __global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kern
                 constexpr int j = decltype(jc)::value;
                 wait_vmcnt<(S - 2) * NLOAD + (j == 1 ? NSC : 0)>();
                 __syncthreads();
-#pragma unroll
-                for (int q = 0; q < NI; ++q) copy_item(src[q] + copy_off, lds0 + cur * STAGE + dst[q]);
                 if (j == 0) {
 #pragma unroll
                     for (int q = 0; q < NSC; ++q) issue_scale_one(q, ks4 + 1, (int)((ks4 + 1) & 1));
                 }
+#pragma unroll
+                for (int q = 0; q < NI; ++q) copy_item(src[q] + copy_off, lds0 + cur * STAGE + dst[q]);
                 cur = cur + 1 == S ? 0 : cur + 1;
                 copy_off = copy_off + kUnitBytes < last_off ? copy_off + kUnitBytes : last_off;
             };
@@ -338,17 +352,20 @@ __global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kern
             // at j == 0 the scale copies of the next group, at j == 3 the read of those scales
             constexpr int NCP = WS ? 0 : NI, NSCP = WS ? 0 : NSC;      // copies issued by this wave
             constexpr int NAUX = (NUA + NUB) + NCP + (j == 0 ? NSCP : 0) + (j == 3 ? 1 : 0);
+            constexpr int NSLOT = NM > MX_SCALED_TAIL_MFMAS ? NM - MX_SCALED_TAIL_MFMAS : 1;
             auto aux = [&](int x) {
                 if (x < NUA + NUB) { read_unit(x, nxt, std::integral_constant<int, set ^ 1>{}); return; }
                 x -= NUA + NUB;
+                if (j == 0) {                             // the scale copies go ahead of the step's data copies
+                    if (x < NSCP) { issue_scale_one(x, ks4 + 1, (int)((ks4 + 1) & 1)); return; }
+                    x -= NSCP;
+                }
                 if (x < NCP) { copy_item(src[x] + copy_off, lds0 + cur * STAGE + dst[x]); return; }
-                x -= NCP;
-                if (j == 0 && NSCP > 0) issue_scale_one(x, ks4 + 1, (int)((ks4 + 1) & 1));
                 if (j == 3) read_scales((int)((ks4 + 1) & 1), nxA, nxB);
             };
             __builtin_amdgcn_sched_barrier(0);
             // newer than D(ks+1): the data copies of the last S-2 steps, and at j == 1 the scale copies
-            // issued at the end of the previous step (at other steps they are simply awaited too)
+            // issued at the previous step, ahead of its data copies (at step 2 they are simply awaited too)
             if constexpr (WS == 0) wait_vmcnt<(S - 2) * NLOAD + (j == 1 ? NSC : 0)>();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
@@ -361,8 +378,12 @@ __global__ __launch_bounds__(WS ? 512 : 256, WS ? 2 : OCC) void gemm_scaled_kern
                 const int sb = (int)(scB[tb] + ((PB == 2 && pb == 0) ? 0x04040404u : 0u));
                 acc[ta][tb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                     operand(fa[set][ta][pa]), operand(fb[set][tb][pb]), acc[ta][tb], 2, 2, j, sa, j, sb);
+                // the side work goes between the first NSLOT MFMAs: the step ends on MFMAs alone, so the LDS reads
+                // have returned by the time the next step's barrier waits for them
+                if (m < NSLOT) {
 #pragma unroll
-                for (int x = m * NAUX / NM; x < (m + 1) * NAUX / NM; ++x) aux(x);
+                    for (int x = m * NAUX / NSLOT; x < (m + 1) * NAUX / NSLOT; ++x) aux(x);
+                }
                 __builtin_amdgcn_sched_barrier(0);        // pin the interleaving as written
             }
             cur = nxt;
@@ -537,7 +558,7 @@ template <int PA, int PB, int QO = 0>
 mx_status pick_tile(ScaledArgs& g, int64_t batch, hipStream_t st) {
     const int64_t tiles = ceil_div(g.M, 128) * ceil_div(g.N, 256) * batch;
     if constexpr (PB == 1) {
-        if (tiles >= 2 * 256) return launch_scaled<PA, PB, 2, 4, 3, 2, QO>(g, batch, st);
+        if (tiles >= MX_SCALED_TWO_PER_CU_TILES) return launch_scaled<PA, PB, 2, 4, 3, 2, QO>(g, batch, st);
         if constexpr (QO == 0) return launch_scaled<PA, PB, 2, 4, 5, 1, 0, 1>(g, batch, st);
         return launch_scaled<PA, PB, 2, 4, 4, 1, QO>(g, batch, st);
     } else {

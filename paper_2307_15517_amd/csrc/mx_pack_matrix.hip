@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void quantize_pack_matrix_kernel(QPackArgs a) 
     for (int r = 0; r < 8; ++r) {
         const int64_t row = rt * 32 + 4 * r + (lane >> 4);
         in[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (row < a.rows && c < a.cols) in[r] = *reinterpret_cast<const float4*>(xb + row * a.row_stride + c);
+        if (row < a.rows && c < a.cols) in[r] = load_once4(xb + row * a.row_stride + c);
     }
 #pragma unroll
     for (int r = 0; r < 8; ++r)
