@@ -901,6 +901,28 @@ def test_matrix_gemm_more_than_one_round_of_tiles_ragged_n(N, wa):
     say("ragged rounds, N", N, "worst", check_product(host(y)[0], y_ref, mag, "ragged rounds N=%d" % N))
 
 
+@pytest.mark.parametrize("wa,wb,block", [(8, 4, 32), (3, 4, 64), (8, 6, 32), (4, 8, 64)])
+def test_matrix_gemm_block_exponents_change_with_every_group_of_k_steps(wa, wb, block):
+    """Small products (one or two tiles: the form with copy waves and the deepest pipeline) repeated many times, the
+    magnitude of both operands moving by a few binades from one group of four K steps (256 elements) to the next, so
+    that scales read for the wrong group, or before their copy has landed, show in every element.  All four piece
+    combinations of the block-scaled kernel; whole output, every repetition."""
+    rng = np.random.default_rng(17 * wa + wb)
+    M, N, K = 100, 300, 13 * 256
+    grp = np.repeat(np.arange(K // 256), 256)
+    x = (rng.standard_normal((M, K)) * np.exp2(((5 * grp) % 11) - 5.0)).astype(np.float32)
+    wt = (rng.standard_normal((N, K)) * 0.02 * np.exp2(((3 * grp) % 7) - 3.0)).astype(np.float32)
+    fa, fb = mx.fmt(block, wa), mx.fmt(block, wb)
+    A, B = mx.quantize_pack(dev(x), fa, MAT), mx.quantize_pack(dev(wt), fb, MAT)
+    y_ref, mag = orc.linear(x, wt, block, wa, wb, want_mag=True)
+    worst = 0.0
+    for rep in range(40):
+        y = mx.gemm(A, fa, B, fb, M, N, K, layout=MAT)
+        torch.cuda.synchronize()
+        worst = max(worst, check_product(host(y)[0], y_ref, mag, "k-group scales, repetition %d" % rep))
+    say("k-group scales", wa, wb, block, "worst", worst)
+
+
 @pytest.mark.parametrize("block", [16, 32, 64])
 @pytest.mark.parametrize("spread", ["window", "adversarial"])
 def test_matrix_gemm_all_width_pairs_ragged_shapes(block, spread):
