@@ -13,7 +13,8 @@
  * Conventions for every entry point
  *   - Pointers named x, y, Y, mant, exps, packed, A_packed, B_packed are DEVICE
  *     pointers (e.g. a torch tensor's data_ptr()).  The library allocates nothing,
- *     frees nothing and never synchronizes: all work is enqueued on `stream` (a
+ *     frees nothing and never synchronizes (mx_check_finite, which returns an answer
+ *     about device data, is the one exception): all work is enqueued on `stream` (a
  *     hipStream_t passed as void*, NULL = default stream).  Between calls it keeps no
  *     data; the only host state is, per kernel that needs more than 64 KB of LDS, a
  *     set of the devices on which that limit has been raised (set once, thread-safe).
@@ -23,6 +24,7 @@
  *     a misaligned pointer.  MX_ERR_UNSUPPORTED: a legal request this library has no
  *     kernel for.  MX_ERR_DEVICE: the HIP runtime refused the launch.
  *   - Inputs must be finite; NaN and infinity give unspecified mantissas (no fault).
+ *     mx_check_finite tests that precondition for callers who want it tested.
  *
  * Canonical form of a quantized tensor of `rows` rows and `cols` columns with the
  * blocks running along the columns (this is the form bit-exactness is stated on):
@@ -139,6 +141,17 @@ MX_API size_t mx_exps_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format
 MX_API mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
                       int64_t batch_stride, int32_t axis, mx_format f, uint8_t* mant, uint8_t* exps,
                       void* stream);
+
+/*
+ * The precondition of the calls that take fp32 input (finite values), checked as a call of its own for callers and
+ * tests that want it; the quantizers themselves do not look (a pass over the input would cost as much as they do).
+ * Returns MX_ERR_BAD_ARG when one of the batch x rows x cols elements, addressed as in mx_quantize, is a NaN or an
+ * infinity, MX_OK when all are finite.  The only entry point that waits: it enqueues its kernels on `stream`, copies
+ * the answer to the host and synchronizes that stream before it returns (so it cannot be captured into a graph).
+ * flag: 4 bytes of caller-owned device memory, 4-byte aligned, overwritten (1 = a non-finite value was found).
+ */
+MX_API mx_status mx_check_finite(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                                 int64_t batch_stride, int32_t* flag, void* stream);
 
 /*
  * Inverse of the quantizer's encoding (Section 3.2 "dequantize"): y[b][r][c] =

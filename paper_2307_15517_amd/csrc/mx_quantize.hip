@@ -437,6 +437,31 @@ mx_status launch_dequant(const DequantArgs& a, hipStream_t st) {
 }  // namespace
 }  // namespace mx
 
+namespace mx {
+namespace {
+
+// One workgroup per 1024-element piece of a row: a lane looks at four elements and the workgroup raises the flag
+// when any of them has all exponent bits set (NaN or infinity).
+__global__ __launch_bounds__(256) void nonfinite_kernel(const float* x, int64_t rows, int64_t cols, int64_t row_stride,
+                                                        int64_t batch_stride, int64_t pieces, int32_t* flag) {
+    const int64_t item = blockIdx.x;
+    const int64_t line = item / pieces, piece = item - line * pieces;
+    const int64_t b = line / rows, r = line - b * rows;
+    const float* row = x + b * batch_stride + r * row_stride;
+    bool bad = false;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t c = piece * 1024 + u * 256 + threadIdx.x;
+        if (c < cols) bad = bad || ((__float_as_uint(row[c]) & 0x7F800000u) == 0x7F800000u);
+    }
+    if (bad) *flag = 1;                       // every writer writes the same value
+}
+
+__global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
+
+}  // namespace
+}  // namespace mx
+
 using namespace mx;
 
 extern "C" size_t mx_mant_bytes(int64_t batch, int64_t rows, int64_t cols, mx_format f) {
@@ -495,6 +520,24 @@ extern "C" mx_status mx_quantize(const float* x, int64_t batch, int64_t rows, in
         MX_SWITCH_W(f.mant_bits, MX_SWITCH_B(f.block, return (launch_axis0<kW, kB>(a, f.rounding, st))));
     }
     return MX_ERR_UNSUPPORTED;
+}
+
+extern "C" mx_status mx_check_finite(const float* x, int64_t batch, int64_t rows, int64_t cols, int64_t row_stride,
+                                     int64_t batch_stride, int32_t* flag, void* stream) {
+    if (batch < 0 || rows < 0 || cols < 0 || row_stride < cols) return MX_ERR_BAD_ARG;
+    if (batch > 1 && batch_stride < (rows - 1) * row_stride + cols) return MX_ERR_BAD_ARG;
+    if (batch == 0 || rows == 0 || cols == 0) return MX_OK;
+    if (!x || !flag || ((uintptr_t)x & 3) || ((uintptr_t)flag & 3)) return MX_ERR_BAD_ARG;
+    const int64_t pieces = ceil_div(cols, 1024), items = batch * rows * pieces;
+    if (items > 0x7fffffffLL) return MX_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    clear_flag_kernel<<<1, 1, 0, st>>>(flag);
+    nonfinite_kernel<<<(uint32_t)items, 256, 0, st>>>(x, rows, cols, row_stride, batch_stride, pieces, flag);
+    if (hipGetLastError() != hipSuccess) return MX_ERR_DEVICE;
+    int32_t found = 0;
+    if (hipMemcpyAsync(&found, flag, sizeof(found), hipMemcpyDeviceToHost, st) != hipSuccess) return MX_ERR_DEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return MX_ERR_DEVICE;
+    return found ? MX_ERR_BAD_ARG : MX_OK;
 }
 
 extern "C" mx_status mx_dequantize(const uint8_t* mant, const uint8_t* exps, int64_t batch, int64_t rows,

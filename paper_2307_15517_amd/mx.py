@@ -20,7 +20,7 @@ MX_OK, MX_ERR_BAD_ARG, MX_ERR_UNSUPPORTED, MX_ERR_DEVICE = 0, 1, 2, 3
 MX_LAYOUT_FRAGMENT = 0
 MX_LAYOUT_MATRIX = 1
 
-EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize",
+EXPORTS = ("mx_version", "mx_status_string", "mx_mant_bytes", "mx_exps_bytes", "mx_quantize", "mx_check_finite",
            "mx_dequantize", "mx_cast", "mx_packed_bytes", "mx_pack", "mx_quantize_pack", "mx_quantize_pack_axis0", "mx_unpack",
            "mx_gemm",
            "mx_gemm_q", "mx_attention", "mx_linear", "mx_linear_workspace_bytes", "mx_linear_static_workspace",
@@ -73,6 +73,7 @@ def load() -> ctypes.CDLL:
     lib.mx_exps_bytes.argtypes, lib.mx_exps_bytes.restype = [i64, i64, i64, mx_format], sz
     lib.mx_quantize.argtypes = [vp, i64, i64, i64, i64, i64, i32, mx_format, vp, vp, vp]
     lib.mx_dequantize.argtypes = [vp, vp, i64, i64, i64, mx_format, vp, vp]
+    lib.mx_check_finite.argtypes, lib.mx_check_finite.restype = [vp, i64, i64, i64, i64, i64, vp, vp], i32
     lib.mx_cast.argtypes = [vp, vp, i64, i64, i64, mx_format, mx_format, vp, vp, vp]
     lib.mx_packed_bytes.argtypes, lib.mx_packed_bytes.restype = [i64, i64, i64, mx_format, i32], sz
     lib.mx_pack.argtypes = [vp, vp, i64, i64, i64, mx_format, i32, vp, vp]
@@ -148,6 +149,11 @@ def mx_quantize(x, batch, rows, cols, row_stride, batch_stride, axis, f, mant, e
     if check:
         _raise(s, "mx_quantize")
     return s
+
+
+def mx_check_finite(x, batch, rows, cols, row_stride, batch_stride, flag, stream=None) -> int:
+    """The status itself is the answer (MX_OK: all finite, MX_ERR_BAD_ARG: a NaN or an infinity, or a bad argument)."""
+    return load().mx_check_finite(_p(x), batch, rows, cols, row_stride, batch_stride, _p(flag), _stream(stream))
 
 
 def mx_dequantize(mant, exps, batch, rows, cols, f, y, stream=None, check: bool = True) -> int:
@@ -289,6 +295,21 @@ def bound(name: str, *args, stream=None):
 
 
 # ---- conveniences that only allocate outputs with torch and call the entry points above -----------
+def check_finite(x: torch.Tensor) -> bool:
+    """True when every element of the float32 CUDA tensor [rows, cols] or [batch, rows, cols] is finite."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.stride(-1) == 1
+    if x.dim() == 2:
+        batch, (rows, cols), bs = 1, x.shape, 0
+    else:
+        batch, rows, cols = x.shape
+        bs = x.stride(0)
+    flag = torch.empty(1, dtype=torch.int32, device=x.device)
+    s = mx_check_finite(x, batch, rows, cols, x.stride(-2), bs, flag)
+    if s not in (MX_OK, MX_ERR_BAD_ARG):
+        _raise(s, "mx_check_finite")
+    return s == MX_OK
+
+
 def quantize(x: torch.Tensor, f: mx_format, axis: int = 1) -> Tuple[torch.Tensor, torch.Tensor]:
     """x: float32 CUDA tensor [rows, cols] or [batch, rows, cols] with contiguous columns."""
     assert x.is_cuda and x.dtype == torch.float32 and x.stride(-1) == 1

@@ -119,6 +119,16 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert att(O=0) == mx.MX_ERR_BAD_ARG
     assert att(obs=31 * 64 + 63) == mx.MX_ERR_BAD_ARG                    # batch stride below (Sq-1)*ldo + D
     assert att(batch=0) == mx.MX_OK
+    # mx_check_finite: its argument checks come before its launches (and before its wait)
+    fin = lambda **kw: mx.mx_check_finite(kw.get("x", 256), kw.get("batch", 1), kw.get("rows", 4), 64, kw.get("rs", 64),
+                                          kw.get("bs", 0), kw.get("flag", 512), stream=0)
+    assert fin(x=0) == mx.MX_ERR_BAD_ARG
+    assert fin(flag=0) == mx.MX_ERR_BAD_ARG
+    assert fin(flag=514) == mx.MX_ERR_BAD_ARG                            # not 4-byte aligned
+    assert fin(x=258) == mx.MX_ERR_BAD_ARG
+    assert fin(rs=32) == mx.MX_ERR_BAD_ARG
+    assert fin(batch=2, bs=100) == mx.MX_ERR_BAD_ARG                     # matrices of the batch would overlap
+    assert fin(rows=0) == mx.MX_OK
     with pytest.raises(mx.MxError):
         mx.mx_quantize(0, 1, 4, 64, 64, 0, 1, f, 256, 256, stream=0)
 

@@ -901,6 +901,34 @@ def test_matrix_gemm_more_than_one_round_of_tiles_ragged_n(N, wa):
     say("ragged rounds, N", N, "worst", check_product(host(y)[0], y_ref, mag, "ragged rounds N=%d" % N))
 
 
+def test_check_finite_agrees_with_what_the_oracle_refuses():
+    """mx_check_finite on a strided batch (rows and matrices with gaps, a ragged last piece of 1024 columns): finite
+    data pass, and a NaN or an infinity of either sign planted anywhere (first and last element included), which the
+    oracle's quantizer refuses, is reported; values in the gaps are not looked at."""
+    rng = np.random.default_rng(77)
+    batch, rows, cols = 3, 37, 2050
+    big = rng.standard_normal((batch, rows + 2, cols + 30)).astype(np.float32)
+    big[:, rows:, :] = np.nan                                   # outside the tensor: rows past the end ...
+    big[:, :, cols:] = np.inf                                   # ... and the gap behind every row
+    bd = dev(big)
+    view = bd[:, :rows, :cols]
+    assert view.stride(-1) == 1 and not view.is_contiguous()
+    assert mx.check_finite(view)
+    assert mx.check_finite(dev(np.full((5, 16), 3.0e38, np.float32)))          # large is not infinite
+    assert mx.check_finite(dev(np.full((5, 16), 1.0e-45, np.float32)))         # nor is a subnormal
+    spots = [(0, 0, 0), (batch - 1, rows - 1, cols - 1), (1, 17, 1023), (1, 17, 1024), (2, 0, 2049)]
+    for (b, r, c), bad in zip(spots, [np.nan, np.inf, -np.inf, -np.nan, np.inf]):
+        keep = float(big[b, r, c])
+        bd[b, r, c] = float(bad)
+        assert not mx.check_finite(view), (b, r, c, bad)
+        one = big[b, :rows, :cols - 2].copy()
+        one[r, min(c, cols - 3)] = bad
+        with pytest.raises(ValueError):
+            orc.quantize(one, 32, 8)
+        bd[b, r, c] = keep
+        assert mx.check_finite(view)
+
+
 @pytest.mark.parametrize("wa,wb,block", [(8, 4, 32), (3, 4, 64), (8, 6, 32), (4, 8, 64)])
 def test_matrix_gemm_block_exponents_change_with_every_group_of_k_steps(wa, wb, block):
     """Small products (one or two tiles: the form with copy waves and the deepest pipeline) repeated many times, the
