@@ -14,6 +14,8 @@
 // ends with 32 partial sums per row.  With more than one slice the partial sums go to the caller's workspace
 // and the workgroup that arrives last at the column group's counter adds them in slice order, so the result
 // does not depend on the order of arrival.
+#include <type_traits>
+
 #include "mx_decode.h"
 #include "mx_frag.h"
 
@@ -249,28 +251,50 @@ void linear_splitk_kernel(DecodeArgs a) {
     __syncthreads();
     if (!is_last) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    // all loads of an output are requested before the first addition (eight slices at a time); the additions
-    // run in slice order whatever the order of arrival was
+    // A thread owns up to OPT outputs of the workgroup's columns.  The loads of all of them, eight or sixteen slices at
+    // a time, are requested before the first addition (one trip to memory for up to sixteen slices, not one per output
+    // or per slice); the additions run in slice order whatever the order of arrival was.  A thread without an output
+    // reads the first partial sum and drops it.
     const uint32_t kstride = (uint32_t)(a.M * np * 4);
-    for (int t = threadIdx.x; t < a.M * (NW * 32); t += T) {
+    constexpr int OPT = (MP * NW * 32 + T - 1) / T;
+    uint32_t off0[OPT];
+    int64_t col_n[OPT];
+    int row_m[OPT];
+    float s[OPT];
+#pragma unroll
+    for (int o = 0; o < OPT; ++o) {
+        const int t = (int)threadIdx.x + o * T;
         const int m = t / (NW * 32), col = t - m * (NW * 32);
         const int64_t nn = (int64_t)gq * (NW * 32) + col;
-        if (nn >= np) continue;
-        const uint32_t off0 = (uint32_t)(((int64_t)m * np + nn) * 4);
-        float s = 0.f;
-        for (int k0 = 0; k0 < a.ksplit; k0 += 8) {
-            uint32_t v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int k = k0 + u < a.ksplit ? k0 + u : a.ksplit - 1;     // a repeated load instead of a branch
-                v[u] = __builtin_amdgcn_raw_buffer_load_b32(rP, off0 + (uint32_t)k * kstride, 0, kDeviceScope);
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (k0 + u < a.ksplit) s += __uint_as_float(v[u]);
-        }
-        if (nn < a.N) a.Y[(int64_t)m * a.ldy + nn] = s;
+        const bool on = m < a.M && nn < np;
+        row_m[o] = on ? m : -1;
+        col_n[o] = nn;
+        off0[o] = on ? (uint32_t)(((int64_t)m * np + nn) * 4) : 0u;
+        s[o] = 0.f;
     }
+    auto add_slices = [&](auto kbc) {                     // KB slices per trip
+        constexpr int KB = decltype(kbc)::value;
+        for (int k0 = 0; k0 < a.ksplit; k0 += KB) {
+            uint32_t v[OPT][KB];
+#pragma unroll
+            for (int o = 0; o < OPT; ++o)
+#pragma unroll
+                for (int u = 0; u < KB; ++u) {
+                    const int k = k0 + u < a.ksplit ? k0 + u : a.ksplit - 1;     // a repeated load instead of a branch
+                    v[o][u] = __builtin_amdgcn_raw_buffer_load_b32(rP, off0[o] + (row_m[o] >= 0 ? (uint32_t)k * kstride : 0u), 0, kDeviceScope);
+                }
+#pragma unroll
+            for (int o = 0; o < OPT; ++o)
+#pragma unroll
+                for (int u = 0; u < KB; ++u)
+                    if (k0 + u < a.ksplit) s[o] += __uint_as_float(v[o][u]);
+        }
+    };
+    if (a.ksplit <= 8) add_slices(std::integral_constant<int, 8>{});
+    else add_slices(std::integral_constant<int, 16>{});
+#pragma unroll
+    for (int o = 0; o < OPT; ++o)
+        if (row_m[o] >= 0 && col_n[o] < a.N) a.Y[(int64_t)row_m[o] * a.ldy + col_n[o]] = s[o];
     if (threadIdx.x == 0) __hip_atomic_store(a.counters + gq, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
